@@ -1,0 +1,123 @@
+"""ctypes wrapper around the CPU oracle (oracle/rtopk_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports this module.
+All arrays are host numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle_rtopk.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    src = os.path.join(_HERE, "rtopk_oracle.cpp")
+    if force or not os.path.exists(_LIB_PATH):
+        subprocess.check_call(
+            ["g++", "-O2", "-std=c++17", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+             "-shared", "-fPIC", src, "-o", _LIB_PATH]
+        )
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB_PATH)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        lib.oracle_topk_exact.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, f32p, i32p]
+        lib.oracle_topk_exact.restype = ctypes.c_int
+        lib.oracle_topk_earlystop_ex.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                 ctypes.c_int32, ctypes.c_int32, f32p, i32p, i32p]
+        lib.oracle_topk_earlystop_ex.restype = ctypes.c_int
+        lib.oracle_alg1.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                    ctypes.c_int32, f32p, i32p, i32p]
+        lib.oracle_alg1.restype = ctypes.c_int
+        lib.oracle_mean_overlap.argtypes = [i32p, i32p, ctypes.c_int64, ctypes.c_int32]
+        lib.oracle_mean_overlap.restype = ctypes.c_double
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def _f32(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _i32(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _check_in(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.ndim != 2:
+        raise ValueError("input must be 2-D [N, M]")
+    return x
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().oracle_set_num_threads(int(n))
+
+
+def topk_exact(x: np.ndarray, k: int):
+    """Plain-definition top-k per row.  Returns (vals [N,k] f32, idx [N,k] i32), columns ascending."""
+    x = _check_in(x)
+    N, M = x.shape
+    vals = np.empty((N, k), dtype=np.float32)
+    idx = np.empty((N, k), dtype=np.int32)
+    rc = _load().oracle_topk_exact(_f32(x), N, M, k, _f32(vals), _i32(idx))
+    if rc != 0:
+        raise ValueError("oracle_topk_exact: bad arguments")
+    return vals, idx
+
+
+def topk_earlystop(x: np.ndarray, k: int, max_iter: int, stop_on_equal: bool = False, return_hit_iter: bool = False):
+    """Algorithm 2, literal (stop_on_equal=False).  stop_on_equal=True is the diagnostic variant."""
+    x = _check_in(x)
+    N, M = x.shape
+    vals = np.empty((N, k), dtype=np.float32)
+    idx = np.empty((N, k), dtype=np.int32)
+    hit = np.empty((N,), dtype=np.int32) if return_hit_iter else None
+    rc = _load().oracle_topk_earlystop_ex(_f32(x), N, M, k, max_iter, 1 if stop_on_equal else 0,
+                                          _f32(vals), _i32(idx), _i32(hit) if hit is not None else None)
+    if rc != 0:
+        raise ValueError("oracle_topk_earlystop: bad arguments")
+    return (vals, idx, hit) if return_hit_iter else (vals, idx)
+
+
+def alg1(x: np.ndarray, k: int, eps_rel: float = 0.0, collect: int = 1, want_select: bool = True,
+         want_iters: bool = True):
+    """Algorithm 1.  Returns (vals, idx, iters); entries not asked for are None."""
+    x = _check_in(x)
+    N, M = x.shape
+    vals = np.empty((N, k), dtype=np.float32) if want_select else None
+    idx = np.empty((N, k), dtype=np.int32) if want_select else None
+    iters = np.empty((N,), dtype=np.int32) if want_iters else None
+    rc = _load().oracle_alg1(_f32(x), N, M, k, eps_rel, collect,
+                             _f32(vals) if want_select else None, _i32(idx) if want_select else None,
+                             _i32(iters) if want_iters else None)
+    if rc != 0:
+        raise ValueError("oracle_alg1: bad arguments")
+    return vals, idx, iters
+
+
+def mean_overlap(idx_a: np.ndarray, idx_b: np.ndarray) -> float:
+    """Mean over rows of |A ∩ B| / k for two [N,k] ascending index arrays (Table 2's Hit)."""
+    a = np.ascontiguousarray(idx_a, dtype=np.int32)
+    b = np.ascontiguousarray(idx_b, dtype=np.int32)
+    assert a.shape == b.shape and a.ndim == 2
+    return float(_load().oracle_mean_overlap(_i32(a), _i32(b), a.shape[0], a.shape[1]))

@@ -1,0 +1,282 @@
+// CPU oracle for batched row-wise top-k selection (RTop-K, arXiv 2409.00822).
+//
+// TEST INFRASTRUCTURE ONLY.  This is the slow, plain reference that the GPU
+// library is checked against.  Only tests, the smoke check and the benchmark's
+// cpu_baseline leg may call it; the product path never does.  It shares no
+// code with the HIP kernels.
+//
+// What is here, and what pins it (see tests/test_oracle_*.py):
+//   oracle_topk_exact      the plain definition of top-k (Section 3.1: with
+//                          epsilon = 0 the method is an exact top-k).  Pinned by
+//                          brute-force stable sorting on tiny tie-heavy rows.
+//   oracle_topk_earlystop  Algorithm 2, step by step, fp32.  Pinned by hand
+//                          traces, by an exact grid-search characterisation on
+//                          dyadic inputs, by its reduction to exact top-k, and
+//                          (through the shared loop, stop_on_equal = 1) by the
+//                          Hit and E1 columns of Table 2.
+//   oracle_alg1            Algorithm 1, step by step, fp32, with the readings
+//                          listed below.  Pinned by Tables 1 and 5 (exit
+//                          iterations), by Eq. 4, and by equality with the
+//                          plain definition at epsilon = 0.
+//
+// Readings of the paper taken here (each is also listed in the design notes):
+//   * midpoint: (min + max) * 0.5f, one rounded fp32 add and an exact halving
+//     (Alg. 1 step "thres <- (min+max)/2"); compiled without contraction or
+//     fast-math so that it is reproducible bit for bit.
+//   * termination at epsilon = 0: the loop also stops when the rounded midpoint
+//     is not strictly inside (min, max); otherwise "while max - min > 0" would
+//     never end once min and max are neighbouring floats.
+//   * collection after such a stop: every element >= max is taken first, then
+//     the lowest-column elements of [min, max) fill up to k.  (Alg. 1's printed
+//     last branch, "first k of v >= thres", can drop a strictly larger element
+//     behind an earlier tied one; Section 3.1 says the borderline elements sit
+//     between min and thres and a second filter on min completes the set.)
+//   * epsilon = epsilon' * |max| so that the guard keeps its meaning for rows
+//     whose maximum is negative.
+//   * ties are broken towards the lower column index; the k outputs are
+//     emitted in ascending column order in every mode.
+//   * iteration t is the t-th midpoint evaluated; a loop that ends through its
+//     guard after t midpoints is recorded as ending at iteration t + 1 (the
+//     failed check of the next trip), as Table 1's 100 % row at 16 implies.
+//
+// Build: g++ -O2 -std=c++17 -fopenmp -ffp-contract=off -shared -fPIC
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <utility>
+#include <vector>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+struct Pair {
+  float v;
+  int32_t i;
+};
+
+// Strict order "a ranks before b": larger value first, then lower column.
+inline bool ranks_before(const Pair& a, const Pair& b) { return a.v > b.v || (a.v == b.v && a.i < b.i); }
+
+inline int32_t count_ge(const float* v, int32_t M, float t) {
+  int32_t c = 0;
+  for (int32_t i = 0; i < M; ++i) c += (v[i] >= t) ? 1 : 0;
+  return c;
+}
+
+inline void row_min_max(const float* v, int32_t M, float& mn, float& mx) {
+  mn = v[0];
+  mx = v[0];
+  for (int32_t i = 1; i < M; ++i) {
+    if (v[i] < mn) mn = v[i];
+    if (v[i] > mx) mx = v[i];
+  }
+}
+
+// Emit, in ascending column order, the first `want` columns i with lo <= v[i] (and v[i] < hi_excl
+// when bounded) into a selection bitmap.
+inline int32_t mark_first(const float* v, int32_t M, float lo, bool bounded, float hi_excl, int32_t want,
+                          std::vector<uint8_t>& sel) {
+  int32_t got = 0;
+  for (int32_t i = 0; i < M && got < want; ++i) {
+    if (v[i] >= lo && (!bounded || v[i] < hi_excl) && !sel[i]) {
+      sel[i] = 1;
+      ++got;
+    }
+  }
+  return got;
+}
+
+inline void emit(const float* v, int32_t M, const std::vector<uint8_t>& sel, int32_t k, float* ov, int32_t* oi) {
+  int32_t j = 0;
+  for (int32_t i = 0; i < M && j < k; ++i)
+    if (sel[i]) {
+      ov[j] = v[i];
+      oi[j] = i;
+      ++j;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
+// Exact top-k by the plain definition: order pairs (v_i, i) by value descending, then column
+// ascending; the first k are the answer, emitted in ascending column order.
+int oracle_topk_exact(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx) {
+  if (N < 0 || M < 1 || k < 1 || k > M) return -1;
+  if (N > 0 && (!in || !out_vals || !out_idx)) return -1;
+#pragma omp parallel
+  {
+    std::vector<Pair> p((size_t)M);
+#pragma omp for schedule(static)
+    for (int64_t r = 0; r < N; ++r) {
+      const float* v = in + r * (int64_t)M;
+      for (int32_t i = 0; i < M; ++i) p[i] = Pair{v[i], i};
+      std::nth_element(p.begin(), p.begin() + k, p.end(), ranks_before);
+      std::sort(p.begin(), p.begin() + k, [](const Pair& a, const Pair& b) { return a.i < b.i; });
+      for (int32_t j = 0; j < k; ++j) {
+        out_vals[r * (int64_t)k + j] = p[j].v;
+        out_idx[r * (int64_t)k + j] = p[j].i;
+      }
+    }
+  }
+  return 0;
+}
+
+// Algorithm 2 (binary search with early stopping), literal, fp32.
+//   min, max of the row; max_iter times: thres = (min+max)/2, cnt = #{v >= thres},
+//   cnt < k -> max = thres, else min = thres; then the first k pairs with v >= min.
+// stop_on_equal = 0 is Algorithm 2 as printed.  stop_on_equal = 1 is a diagnostic variant in which
+// an iteration with cnt == k ends the search without moving min (the three-way branch of
+// Algorithm 1); it exists only to show that Table 2's columns are reproduced by the same loop.
+// out_hit_iter (optional, one per row): first iteration (1-based) at which cnt == k was seen, 0 if never.
+int oracle_topk_earlystop_ex(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter,
+                             int32_t stop_on_equal, float* out_vals, int32_t* out_idx, int32_t* out_hit_iter) {
+  if (N < 0 || M < 1 || k < 1 || k > M || max_iter < 0) return -1;
+  if (N > 0 && (!in || !out_vals || !out_idx)) return -1;
+#pragma omp parallel
+  {
+    std::vector<uint8_t> sel((size_t)M);
+#pragma omp for schedule(static)
+    for (int64_t r = 0; r < N; ++r) {
+      const float* v = in + r * (int64_t)M;
+      float mn, mx;
+      row_min_max(v, M, mn, mx);
+      int32_t hit = 0;
+      for (int32_t iter = 1; iter <= max_iter; ++iter) {
+        const float thres = (mn + mx) * 0.5f;
+        const int32_t cnt = count_ge(v, M, thres);
+        if (cnt == k && hit == 0) hit = iter;
+        if (cnt < k) {
+          mx = thres;
+        } else if (stop_on_equal && cnt == k) {
+          break;
+        } else {
+          mn = thres;
+        }
+      }
+      std::fill(sel.begin(), sel.end(), (uint8_t)0);
+      mark_first(v, M, mn, false, 0.0f, k, sel);
+      emit(v, M, sel, k, out_vals + r * (int64_t)k, out_idx + r * (int64_t)k);
+      if (out_hit_iter) out_hit_iter[r] = hit;
+    }
+  }
+  return 0;
+}
+
+int oracle_topk_earlystop(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
+                          int32_t* out_idx) {
+  return oracle_topk_earlystop_ex(in, N, M, k, max_iter, 0, out_vals, out_idx, nullptr);
+}
+
+// Algorithm 1 (binary search until cnt == k or the interval is narrower than epsilon), fp32.
+//   eps_rel    epsilon' of the paper; epsilon = epsilon' * |max|.  0 gives the exact mode.
+//   collect    0: the collection step exactly as printed (uses the last thres and cnt);
+//              1: the reading described at the top of this file (all v >= max, then fill from
+//                 [min, max) by column), which is what makes epsilon = 0 exact under ties.
+//   out_iters  (optional) exit iteration per row, numbered as described at the top.
+//   out_vals / out_idx may both be null when only the iteration counts are wanted.
+int oracle_alg1(const float* in, int64_t N, int32_t M, int32_t k, float eps_rel, int32_t collect, float* out_vals,
+                int32_t* out_idx, int32_t* out_iters) {
+  if (N < 0 || M < 1 || k < 1 || k > M || !(eps_rel >= 0.0f)) return -1;
+  if (N > 0 && !in) return -1;
+  if ((out_vals == nullptr) != (out_idx == nullptr)) return -1;
+#pragma omp parallel
+  {
+    std::vector<uint8_t> sel((size_t)M);
+#pragma omp for schedule(static)
+    for (int64_t r = 0; r < N; ++r) {
+      const float* v = in + r * (int64_t)M;
+      float mn, mx;
+      row_min_max(v, M, mn, mx);
+      const float eps = eps_rel * std::fabs(mx);
+      int32_t cnt = 0;
+      float thres = mn;  // Alg. 1 reads thres after a loop that may not have run; then min == max.
+      int32_t t = 0;     // midpoints evaluated so far
+      bool hit = false;
+      while (mx - mn > eps) {
+        const float mid = (mn + mx) * 0.5f;
+        if (!(mid > mn && mid < mx)) break;  // no float strictly inside: the search cannot narrow further
+        thres = mid;
+        ++t;
+        cnt = count_ge(v, M, thres);
+        if (cnt < k) {
+          mx = thres;
+        } else if (cnt > k) {
+          mn = thres;
+        } else {
+          hit = true;
+          break;
+        }
+      }
+      if (out_iters) out_iters[r] = hit ? t : t + 1;
+      if (!out_vals) continue;
+
+      std::fill(sel.begin(), sel.end(), (uint8_t)0);
+      if (hit) {
+        mark_first(v, M, thres, false, 0.0f, k, sel);
+      } else if (collect == 0) {
+        if (t == 0) cnt = count_ge(v, M, thres);  // loop body never ran: thres == min, cnt == M
+        if (cnt < k) {
+          const int32_t got = mark_first(v, M, thres, false, 0.0f, M, sel);
+          mark_first(v, M, mn, true, thres, k - got, sel);
+        } else {
+          mark_first(v, M, thres, false, 0.0f, k, sel);
+        }
+      } else {
+        const int32_t got = mark_first(v, M, mx, false, 0.0f, k, sel);
+        mark_first(v, M, mn, true, mx, k - got, sel);
+      }
+      emit(v, M, sel, k, out_vals + r * (int64_t)k, out_idx + r * (int64_t)k);
+    }
+  }
+  return 0;
+}
+
+// Fraction of overlap |A ∩ B| / k between two index sets per row, averaged over rows ("Hit" of
+// Table 2).  Both inputs are [N][k] with ascending columns per row.
+double oracle_mean_overlap(const int32_t* a, const int32_t* b, int64_t N, int32_t k) {
+  if (N <= 0 || k < 1) return 0.0;
+  double total = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : total)
+  for (int64_t r = 0; r < N; ++r) {
+    const int32_t* x = a + r * (int64_t)k;
+    const int32_t* y = b + r * (int64_t)k;
+    int32_t i = 0, j = 0, c = 0;
+    while (i < k && j < k) {
+      if (x[i] == y[j]) {
+        ++c;
+        ++i;
+        ++j;
+      } else if (x[i] < y[j]) {
+        ++i;
+      } else {
+        ++j;
+      }
+    }
+    total += (double)c / (double)k;
+  }
+  return total / (double)N;
+}
+
+}  // extern "C"
