@@ -1,0 +1,90 @@
+/*
+ * rtopk.h -- C ABI of the MI355X (gfx950) row-wise top-k library.
+ *
+ * Operation (RTop-K paper, arXiv 2409.00822, Section 3: problem statement and Algorithms 1 and 2):
+ * for each of N rows of M fp32 values, select k (value, column) pairs by a binary search over a
+ * threshold between the row's minimum and maximum, counting the elements at or above each midpoint.
+ *
+ * Common conventions for every entry point below
+ * ----------------------------------------------
+ *  - All data pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ *    frees, copies to the host or synchronises.  Work is enqueued on `stream` (a hipStream_t passed
+ *    as void*; NULL means the default stream) and the call returns at once.
+ *  - `in`       : [N][M] fp32, dense, row-major, row stride M, read-only, 4-byte aligned.
+ *                 Rows are processed fastest when `in` is 16-byte aligned and M is a multiple of 4;
+ *                 other shapes take a scalar-load path with the same results.
+ *  - `out_vals` : [N][k] fp32, row-major.  out_vals[r][j] is the bit pattern of in[r][out_idx[r][j]].
+ *  - `out_idx`  : [N][k] column indices, 0-based, strictly ascending within a row
+ *                 (int32_t, or uint8_t in the *_u8 variants, which require M <= 256: this is the
+ *                 compressed row -- k values plus k byte-wide columns -- that MaxK-GNN's sparse
+ *                 aggregation consumes, Section 1 / Fig. 1).
+ *  - Input and output buffers must not overlap.
+ *  - Ties are broken towards the lower column index.
+ *  - Preconditions that are NOT checked: every input is finite and |v| < FLT_MAX / 2 (so that
+ *    min + max cannot overflow).  With NaN or infinities the selection is unspecified, but the call
+ *    still terminates and writes only inside the output buffers.
+ *  - Return value: RTOPK_OK (0) when the work was enqueued (or N == 0: nothing to do), otherwise a
+ *    negative RTOPK_ERR_* code; every argument check happens on the host before any launch, and on
+ *    error nothing was enqueued.  Faults of the asynchronous work surface at the caller's next
+ *    synchronisation, as with any HIP launch.
+ *  - Limits: 1 <= k <= M <= rtopk_max_m(); 0 <= N; N * M and N * k must fit in int64_t.
+ */
+#ifndef RTOPK_H_
+#define RTOPK_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  RTOPK_OK = 0,
+  RTOPK_ERR_NULL_POINTER = -1,  /* a data pointer is NULL while N > 0 */
+  RTOPK_ERR_BAD_SHAPE = -2,     /* N < 0, M < 1, k < 1 or k > M */
+  RTOPK_ERR_BAD_MAX_ITER = -3,  /* max_iter < 0 */
+  RTOPK_ERR_M_TOO_LARGE = -4,   /* M > rtopk_max_m(), or M > 256 in a *_u8 variant */
+  RTOPK_ERR_MISALIGNED = -5,    /* a pointer is not aligned to its element size */
+  RTOPK_ERR_LAUNCH = -6,        /* the HIP runtime refused the launch */
+  RTOPK_ERR_BAD_EPSILON = -7    /* eps_rel is negative or NaN */
+};
+
+/*
+ * Early-stopping selection: Algorithm 2 (Section 3.1), taken literally.
+ *   lo = min(row), hi = max(row); repeat max_iter times: thres = (lo + hi) * 0.5f in fp32,
+ *   cnt = #{v >= thres}, cnt < k ? hi = thres : lo = thres; emit the first k columns with v >= lo.
+ * max_iter == 0 is legal and returns the first k columns.  The result is bit-identical to a scalar
+ * fp32 evaluation of those steps.
+ */
+int rtopk_rowwise(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
+                  int32_t* out_idx, void* stream);
+
+/*
+ * Exact selection: Algorithm 1 with epsilon = 0 (Section 3.1: "becomes an exact top-k selection").
+ * The search runs until an iteration counts exactly k elements, or until no fp32 value lies strictly
+ * between lo and hi; then everything >= hi is taken and the lowest columns of [lo, hi) fill up to k.
+ * The result equals the plain definition of top-k with the lower column winning ties.
+ */
+int rtopk_rowwise_exact(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx,
+                        void* stream);
+
+/* The same two operations writing uint8_t columns (MaxK compressed row layout); require M <= 256. */
+int rtopk_rowwise_u8(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
+                     uint8_t* out_idx, void* stream);
+int rtopk_rowwise_exact_u8(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, uint8_t* out_idx,
+                           void* stream);
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* rtopk_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int rtopk_version(void);
+
+/* Largest supported row width M. */
+int rtopk_max_m(void);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* RTOPK_H_ */

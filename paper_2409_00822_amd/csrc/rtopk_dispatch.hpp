@@ -1,0 +1,27 @@
+// Host-side dispatch table between the C ABI (rtopk_api.hip) and the kernel instantiations, which
+// are spread over several translation units so that they compile in parallel.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rtopk {
+
+struct LaunchArgs {
+  const float* in;
+  int64_t N;
+  int M, k, max_iter;
+  float* out_vals;
+  void* out_idx;
+  int vec_store;  // 1: k % 4 == 0 and both outputs aligned for 128-bit (values) / whole-word (columns) stores
+  hipStream_t stream;
+};
+
+// Vector-load paths: M % G == 0 and `in` aligned to 4*G bytes.  ng = groups per lane (M <= 64*G*ng).
+// full = (M == 64*G*ng): no column-validity tests in the kernel.
+hipError_t launch_g4_exact(int ng, bool full, bool u8, const LaunchArgs& a);
+hipError_t launch_g4_early(int ng, bool full, bool u8, const LaunchArgs& a);
+// Narrow rows and scalar-load fallback (any M, 4-byte alignment).
+hipError_t launch_small(int g, int ng, bool full, bool exact, bool u8, const LaunchArgs& a);
+
+}  // namespace rtopk

@@ -1,0 +1,29 @@
+// Instantiations: 128-bit-load path (G = 4), early mode.
+#include "rtopk_kernel.hpp"
+
+namespace rtopk {
+
+template <int NG>
+static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
+  constexpr int R = rows_per_wave(4 * NG);
+  if constexpr (NG == 1) {
+    if (u8) return full ? launch<4, NG, R, true, false, uint8_t>(a) : launch<4, NG, R, false, false, uint8_t>(a);
+  }
+  return full ? launch<4, NG, R, true, false, int32_t>(a) : launch<4, NG, R, false, false, int32_t>(a);
+}
+
+hipError_t launch_g4_early(int ng, bool full, bool u8, const LaunchArgs& a) {
+  switch (ng) {
+    case 1: return pick<1>(full, u8, a);
+    case 2: return pick<2>(full, u8, a);
+    case 3: return pick<3>(full, u8, a);
+    case 4: return pick<4>(full, u8, a);
+    case 6: return pick<6>(full, u8, a);
+    case 8: return pick<8>(full, u8, a);
+    case 12: return pick<12>(full, u8, a);
+    case 16: return pick<16>(full, u8, a);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace rtopk

@@ -1,0 +1,115 @@
+"""ctypes binding with the same names as the C ABI (include/rtopk.h).  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librtopk.so")
+_lib = None
+
+
+class RTopKError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"rtopk status {status}: {text}")
+        self.status = status
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load librtopk.so (built by `python -m paper_2409_00822_amd.build` or __graft_entry__.build()).
+    Raises if it is missing: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} not found: build it with `python -m paper_2409_00822_amd.build`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        lib.rtopk_rowwise.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+        lib.rtopk_rowwise_u8.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+        lib.rtopk_rowwise_exact.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        lib.rtopk_rowwise_exact_u8.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        for fn in (lib.rtopk_rowwise, lib.rtopk_rowwise_u8, lib.rtopk_rowwise_exact, lib.rtopk_rowwise_exact_u8,
+                   lib.rtopk_version, lib.rtopk_max_m):
+            fn.restype = ctypes.c_int
+        lib.rtopk_status_string.argtypes = [ctypes.c_int]
+        lib.rtopk_status_string.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def rtopk_status_string(status: int) -> str:
+    return load_library().rtopk_status_string(int(status)).decode()
+
+
+def rtopk_version() -> int:
+    return int(load_library().rtopk_version())
+
+
+def rtopk_max_m() -> int:
+    return int(load_library().rtopk_max_m())
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise RTopKError(status, rtopk_status_string(status))
+
+
+def _prepare(x, k: int, out_vals, out_idx, idx_dtype):
+    import torch
+
+    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.is_contiguous()):
+        raise ValueError("x must be a contiguous 2-D float32 tensor on the GPU")
+    N, M = x.shape
+    if out_vals is None:
+        out_vals = torch.empty((N, k), dtype=torch.float32, device=x.device)
+    if out_idx is None:
+        out_idx = torch.empty((N, k), dtype=idx_dtype, device=x.device)
+    for t, dt in ((out_vals, torch.float32), (out_idx, idx_dtype)):
+        if not (t.is_cuda and t.dtype == dt and t.is_contiguous() and tuple(t.shape) == (N, k)):
+            raise ValueError("outputs must be contiguous [N, k] GPU tensors of the right dtype")
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    return N, M, out_vals, out_idx, stream
+
+
+def rtopk_rowwise(x, k: int, max_iter: int, out_vals=None, out_idx=None):
+    """Algorithm 2 (early stopping).  Returns (values [N,k] f32, columns [N,k] i32)."""
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.int32)
+    _check(load_library().rtopk_rowwise(x.data_ptr(), N, M, k, max_iter, out_vals.data_ptr(), out_idx.data_ptr(),
+                                        stream))
+    return out_vals, out_idx
+
+
+def rtopk_rowwise_exact(x, k: int, out_vals=None, out_idx=None):
+    """Algorithm 1 at epsilon = 0 (exact top-k).  Returns (values [N,k] f32, columns [N,k] i32)."""
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.int32)
+    _check(load_library().rtopk_rowwise_exact(x.data_ptr(), N, M, k, out_vals.data_ptr(), out_idx.data_ptr(), stream))
+    return out_vals, out_idx
+
+
+def rtopk_rowwise_u8(x, k: int, max_iter: int, out_vals=None, out_idx=None):
+    """Algorithm 2 with uint8 columns (M <= 256)."""
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.uint8)
+    _check(load_library().rtopk_rowwise_u8(x.data_ptr(), N, M, k, max_iter, out_vals.data_ptr(), out_idx.data_ptr(),
+                                           stream))
+    return out_vals, out_idx
+
+
+def rtopk_rowwise_exact_u8(x, k: int, out_vals=None, out_idx=None):
+    """Exact top-k with uint8 columns (M <= 256)."""
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.uint8)
+    _check(load_library().rtopk_rowwise_exact_u8(x.data_ptr(), N, M, k, out_vals.data_ptr(), out_idx.data_ptr(),
+                                                 stream))
+    return out_vals, out_idx

@@ -1,0 +1,229 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: column indices bit-exact, values bit-exact copies (tolerance 0), in both modes.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2409_00822_amd as R
+
+    R.load_library()  # fails loudly if the HIP library is not built
+    return R
+
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.int32)
+
+
+def run_gpu(R, x_np, k, mode, max_iter=0, u8=False, x_dev=None):
+    x = torch.from_numpy(x_np).cuda() if x_dev is None else x_dev
+    if mode == "exact":
+        v, i = (R.rtopk_rowwise_exact_u8 if u8 else R.rtopk_rowwise_exact)(x, k)
+    else:
+        v, i = (R.rtopk_rowwise_u8 if u8 else R.rtopk_rowwise)(x, k, max_iter)
+    torch.cuda.synchronize()
+    return v.cpu().numpy(), i.cpu().numpy()
+
+
+def run_oracle(x_np, k, mode, max_iter=0):
+    if mode == "exact":
+        return oracle.topk_exact(x_np, k)
+    return oracle.topk_earlystop(x_np, k, max_iter)
+
+
+def assert_parity(R, x_np, k, mode, max_iter=0, u8=False, tag=""):
+    gv, gi = run_gpu(R, x_np, k, mode, max_iter, u8)
+    ov, oi = run_oracle(x_np, k, mode, max_iter)
+    gi32 = gi.astype(np.int32)
+    if not np.array_equal(gi32, oi):
+        bad = np.nonzero((gi32 != oi).any(axis=1))[0]
+        r = int(bad[0])
+        raise AssertionError(f"{tag} index mismatch in {bad.size} rows; first row {r}: gpu {gi32[r]} oracle {oi[r]}")
+    assert np.array_equal(bits(gv), bits(ov)), f"{tag} value bits differ"
+
+
+# ----------------------------------------------------------------------------------------------
+# small shapes: several tiles, ragged tails, every load path
+# ----------------------------------------------------------------------------------------------
+SHAPES = [
+    # (N, M, ks)
+    (1, 1, (1,)), (5, 2, (1, 2)), (9, 7, (1, 3, 7)), (33, 63, (1, 8, 63)), (64, 64, (1, 5, 16, 64)),
+    (65, 65, (3, 65)), (100, 100, (10, 12)), (257, 128, (1, 16, 20, 128)), (31, 130, (13,)),
+    (77, 200, (25, 32)), (4099, 256, (1, 16, 31, 32, 64, 128, 255, 256)), (50, 260, (33, 64)),
+    (130, 300, (32,)), (515, 512, (64, 100)), (129, 768, (96,)), (40, 1000, (125, 128)),
+    (259, 1024, (128, 1000)), (33, 1500, (200,)), (67, 2048, (256,)), (35, 3000, (64,)),
+    (70, 4096, (64, 256, 1024)), (9, 4095, (7, 512)), (17, 1021, (17,)),
+]
+
+
+@pytest.mark.parametrize("N,M,ks", SHAPES)
+def test_exact_small_shapes(N, M, ks):
+    R = _gpu()
+    x = workloads.normal(N, M, seed=N * 7919 + M)
+    for k in ks:
+        assert_parity(R, x, k, "exact", tag=f"N={N} M={M} k={k}")
+
+
+@pytest.mark.parametrize("N,M,ks", SHAPES)
+def test_earlystop_small_shapes(N, M, ks):
+    R = _gpu()
+    x = workloads.normal(N, M, seed=N * 104729 + M)
+    for k in ks:
+        for mi in (0, 1, 2, 4, 8, 16, 40):
+            assert_parity(R, x, k, "early", mi, tag=f"N={N} M={M} k={k} max_iter={mi}")
+
+
+@pytest.mark.parametrize("M", [3, 8, 17, 64, 128, 256, 512, 1024])
+def test_tie_heavy_rows(M):
+    R = _gpu()
+    for gen, seed in (("pool", 61), ("ints", 62)):
+        x = workloads.from_pool(700, M, seed + M) if gen == "pool" else workloads.small_ints(700, M, seed + M, span=3)
+        for k in sorted({1, 2, max(1, M // 8), M // 2 or 1, M - 1 or 1, M}):
+            assert_parity(R, x, k, "exact", tag=f"{gen} M={M} k={k}")
+            for mi in (0, 3, 8, 30):
+                assert_parity(R, x, k, "early", mi, tag=f"{gen} M={M} k={k} mi={mi}")
+
+
+def test_all_equal_and_two_valued_rows():
+    R = _gpu()
+    x = np.full((40, 256), 3.25, dtype=np.float32)
+    x[20:, ::3] = -1.5
+    x[30:, 5] = 7.0
+    for k in (1, 32, 85, 86, 200, 256):
+        assert_parity(R, x, k, "exact", tag=f"const k={k}")
+        assert_parity(R, x, k, "early", 8, tag=f"const k={k}")
+
+
+@pytest.mark.parametrize("M,k", [(256, 32), (128, 16), (200, 24), (64, 8), (100, 7), (255, 33)])
+def test_uint8_columns(M, k):
+    R = _gpu()
+    x = workloads.normal_ties(3001, M, seed=70 + M, p=0.2)
+    assert_parity(R, x, k, "exact", u8=True, tag=f"u8 M={M} k={k}")
+    assert_parity(R, x, k, "early", 8, u8=True, tag=f"u8 M={M} k={k}")
+
+
+def test_unaligned_input_and_output_pointers_take_the_scalar_paths():
+    R = _gpu()
+    N, M, k = 300, 256, 32
+    x = workloads.normal(N, M, seed=81)
+    buf = torch.empty(N * M + 1, dtype=torch.float32, device="cuda")
+    xd = buf[1:].view(N, M)  # 4-byte aligned only
+    xd.copy_(torch.from_numpy(x))
+    ob = torch.empty(N * k + 1, dtype=torch.float32, device="cuda")
+    ib = torch.empty(N * k + 1, dtype=torch.int32, device="cuda")
+    ov, oi = ob[1:].view(N, k), ib[1:].view(N, k)
+    R.rtopk_rowwise_exact(xd, k, ov, oi)
+    torch.cuda.synchronize()
+    ev, ei = oracle.topk_exact(x, k)
+    assert np.array_equal(oi.cpu().numpy(), ei) and np.array_equal(bits(ov.cpu().numpy()), bits(ev))
+    R.rtopk_rowwise(xd, k, 5, ov, oi)
+    torch.cuda.synchronize()
+    sv, si = oracle.topk_earlystop(x, k, 5)
+    assert np.array_equal(oi.cpu().numpy(), si) and np.array_equal(bits(ov.cpu().numpy()), bits(sv))
+
+
+def test_writes_stay_inside_the_outputs_and_nonfinite_inputs_terminate():
+    R = _gpu()
+    N, M, k = 1000, 256, 32
+    x = workloads.normal(N, M, seed=82)
+    x[::7, 3] = np.inf
+    x[::11, 9] = -np.inf
+    x[::13, 100] = np.nan
+    x[5] = np.nan
+    x[6] = np.inf
+    pad = 4096
+    vbuf = torch.full((N * k + 2 * pad,), 12345.0, dtype=torch.float32, device="cuda")
+    ibuf = torch.full((N * k + 2 * pad,), -77, dtype=torch.int32, device="cuda")
+    ov = vbuf[pad:pad + N * k].view(N, k)
+    oi = ibuf[pad:pad + N * k].view(N, k)
+    xd = torch.from_numpy(x).cuda()
+    for call in (lambda: R.rtopk_rowwise_exact(xd, k, ov, oi), lambda: R.rtopk_rowwise(xd, k, 8, ov, oi)):
+        call()
+        torch.cuda.synchronize()
+        assert (vbuf[:pad] == 12345.0).all() and (vbuf[-pad:] == 12345.0).all()
+        assert (ibuf[:pad] == -77).all() and (ibuf[-pad:] == -77).all()
+    # rows without non-finite values are still exact
+    clean = np.isfinite(x).all(axis=1)
+    R.rtopk_rowwise_exact(xd, k, ov, oi)
+    torch.cuda.synchronize()
+    _, ei = oracle.topk_exact(x[clean], k)
+    assert np.array_equal(oi.cpu().numpy()[clean], ei)
+
+
+def test_empty_batch_and_error_codes_on_device():
+    R = _gpu()
+    x = torch.empty((0, 256), dtype=torch.float32, device="cuda")
+    v, i = R.rtopk_rowwise_exact(x, 32)
+    assert v.shape == (0, 32) and i.shape == (0, 32)
+    y = torch.zeros((4, 8), dtype=torch.float32, device="cuda")
+    with pytest.raises(R.RTopKError):
+        R.rtopk_rowwise(y, 3, -1)
+
+
+def test_other_stream():
+    R = _gpu()
+    x = workloads.normal(5000, 256, seed=83)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        xd = torch.from_numpy(x).cuda()
+        v, i = R.rtopk_rowwise_exact(xd, 32)
+    s.synchronize()
+    _, ei = oracle.topk_exact(x, 32)
+    assert np.array_equal(i.cpu().numpy(), ei)
+
+
+# ----------------------------------------------------------------------------------------------
+# the five configurations at full size, in the launch configuration the benchmark times
+# ----------------------------------------------------------------------------------------------
+def _full(name, k, mode, max_iter=0):
+    R = _gpu()
+    cfg = workloads.CONFIGS[name]
+    x = workloads.make(name)
+    assert_parity(R, x, k, mode, max_iter, u8=(cfg["idx"] == "uint8"), tag=f"{name} k={k} {mode} {max_iter}")
+
+
+def test_config0_small():
+    _full("c0_small", 32, "exact")
+    _full("c0_small", 32, "early", 8)
+
+
+def test_config1_maxk_full_size():
+    R = _gpu()
+    x = workloads.make("c1_maxk")
+    xd = torch.from_numpy(x).cuda()
+    for k in (16, 32, 64, 128):
+        gv, gi = run_gpu(R, x, k, "exact", x_dev=xd)
+        ov, oi = oracle.topk_exact(x, k)
+        assert np.array_equal(gi, oi), f"c1 exact k={k}"
+        assert np.array_equal(bits(gv), bits(ov))
+        for mi in (4, 8, 16):
+            gv, gi = run_gpu(R, x, k, "early", mi, x_dev=xd)
+            ov, oi = oracle.topk_earlystop(x, k, mi)
+            assert np.array_equal(gi, oi), f"c1 early k={k} max_iter={mi}"
+            assert np.array_equal(bits(gv), bits(ov))
+
+
+@pytest.mark.parametrize("name", ["c2_w128", "c2_w512", "c2_w1024"])
+def test_config2_width_sweep_full_size(name):
+    _full(name, workloads.CONFIGS[name]["ks"][0], "exact")
+
+
+def test_config3_ties_uint8_full_size():
+    _full("c3_ties", 32, "exact")
+    _full("c3_ties", 32, "early", 8)
+
+
+def test_config4_wide_rows_full_size():
+    _full("c4_wide", 64, "exact")
+    _full("c4_wide", 256, "exact")
