@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--max-iter", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="also run a plain device copy of the input (1 read + 1 write of N*M*4 bytes) a few times: "
+                         "the known-size kernel that scales the profiler's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (rows are independent; see the design notes on "
@@ -94,6 +97,13 @@ def main():
     wall_s, launch_s, _ = time_calls(torch, early, args.steps, args.warmup)
     log(f"  early: {wall_s / args.steps * 1e6:.1f} us/step wall, {launch_s * 1e6:.1f} us/launch (events)")
 
+    if args.with_copy:
+        y = torch.empty_like(x)
+        for _ in range(5):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        del y
+
     parity = None
     recall = None
     cpu = None
@@ -117,13 +127,13 @@ def main():
     if not args.no_cpu_baseline:
         log("timing the CPU oracle (exact mode) on the same input ...")
         reps = []
-        for _ in range(4):
+        for _ in range(9):
             t0 = time.perf_counter()
             oracle.topk_exact(x_host, k)
             reps.append(time.perf_counter() - t0)
         t_cpu = statistics.median(reps[1:])
         cpu = {"value": N / t_cpu, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"all {N} rows of the same input, exact mode (nth_element), median of 3 after 1 warm-up"}
+               "sample": f"all {N} rows of the same input, exact mode (nth_element), median of 8 after 1 warm-up"}
         log(f"  oracle: {t_cpu:.3f} s per pass on {cpu['cores']} threads")
 
     rows_per_s = N * args.steps / wall_e
