@@ -29,87 +29,146 @@ constexpr int kWave = 64;
 
 // ---- cross-lane helpers ---------------------------------------------------------------------------
 
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_move(float keep, float src) {
-  return __int_as_float(
-      __builtin_amdgcn_update_dpp(__float_as_int(keep), __float_as_int(src), CTRL, ROW_MASK, 0xf, false));
-}
-
-// v_min_f32 / v_max_f32 on finite data; written as asm so that no NaN-quieting canonicalisation is
-// added around values that come straight from memory.
-__device__ __forceinline__ float vmin(float a, float b) {
-  float r;
-  asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
+// v_max_f32 with optional source negation, written as asm so that no NaN-quieting canonicalisation
+// is added around values that come straight from memory.
 __device__ __forceinline__ float vmax(float a, float b) {
   float r;
   asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
   return r;
 }
+__device__ __forceinline__ float vmax_an(float a, float b) {  // max(a, -b)
+  float r;
+  asm("v_max_f32_e64 %0, %1, -%2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float vmax_nn(float a, float b) {  // max(-a, -b) = -min(a, b)
+  float r;
+  asm("v_max_f32_e64 %0, -%1, -%2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
 
-// Butterfly inside each row of 16 lanes, then two row broadcasts; lane 63 ends up with the result.
-template <bool IS_MAX>
-__device__ __forceinline__ float wave_reduce(float v) {
-  auto op = [](float a, float b) { return IS_MAX ? vmax(a, b) : vmin(a, b); };
-  v = op(v, dpp_move<0xB1, 0xf>(v, v));   // quad_perm [1,0,3,2]
-  v = op(v, dpp_move<0x4E, 0xf>(v, v));   // quad_perm [2,3,0,1]
-  v = op(v, dpp_move<0x141, 0xf>(v, v));  // row_half_mirror
-  v = op(v, dpp_move<0x140, 0xf>(v, v));  // row_mirror
-  v = op(v, dpp_move<0x142, 0xa>(v, v));  // row_bcast:15 into rows 1 and 3
-  v = op(v, dpp_move<0x143, 0xc>(v, v));  // row_bcast:31 into rows 2 and 3
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+// Row maximum and minimum in one reduction.  On entry every lane holds mx = max of its elements and
+// nm = max of its negated elements.  The two halves of the wavefront are swapped so that lanes 0..31
+// reduce the maxima and lanes 32..63 the negated minima with the same five DPP steps.
+__device__ __forceinline__ void wave_max_and_negmin(float mx, float nm, float& hi, float& lo) {
+  asm("s_nop 1\n\t"
+      "v_permlane32_swap_b32 %0, %1\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32 %0, %0, %1\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(mx), "+v"(nm));
+  hi = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 31));
+  lo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 63) ^ (int)0x80000000);
 }
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask, uint32_t add) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, add));
 }
 
+// p + (bit `lane` of mask): one add-with-carry whose carry-in is the lane mask.
+__device__ __forceinline__ uint32_t add_mask_bit(uint32_t p, uint64_t mask) {
+  uint32_t r;
+  asm("v_addc_co_u32_e64 %0, vcc, %1, 0, %2" : "=v"(r) : "v"(p), "s"(mask) : "vcc");
+  return r;
+}
+
+// In the lanes whose bit is set in `mask`: LDS[addr] = a, LDS[addr + 4] = b.  The kernel runs with
+// all 64 lanes active whenever this is called, so EXEC is restored to all ones.
+__device__ __forceinline__ void lds_store_pair_masked(uint64_t mask, uint32_t addr, uint32_t a, uint32_t b) {
+  asm volatile(
+      "s_mov_b64 exec, %0\n\t"
+      "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
+      "s_mov_b64 exec, -1"
+      :
+      : "s"(mask), "v"(addr), "v"(a), "v"(b)
+      : "memory");
+}
+
+// if (cnt < k) hi = t; else lo = t;   (all operands wave-uniform)
+__device__ __forceinline__ void move_bound(float& lo, float& hi, float t, int cnt, int k) {
+  const bool less = cnt < k;
+  hi = less ? t : hi;
+  lo = less ? lo : t;
+}
+
 // ---- one row ----------------------------------------------------------------------------------------
 
 // cnt = #{e, lane : x[e] >= t}.  The compare writes a 64-lane mask to scalar registers; the count is
-// a scalar popcount, so no cross-lane reduction is needed.
+// a scalar popcount, so no cross-lane reduction is needed.  m[e] keeps the masks.
 template <int E>
-__device__ __forceinline__ int count_ge(const float (&x)[E], float t) {
+__device__ __forceinline__ int count_ge(const float (&x)[E], float t, uint64_t (&m)[E]) {
   int cnt = 0;
 #pragma unroll
-  for (int e = 0; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= t));
+  for (int e = 0; e < E; ++e) {
+    m[e] = __builtin_amdgcn_ballot_w64(x[e] >= t);
+    cnt += __builtin_popcountll(m[e]);
+  }
   return cnt;
 }
 
-// Selecting stage.  An element is a candidate of class A when x >= ta, of class B when tb <= x < ta.
-// All of A is wanted first (cut at `limit`, in column order), then the first `need_b` members of B in
-// column order.  The chosen pairs are written to stage[0 .. ) in ascending column order
-// (g, lane, c).  With need_b == 0 this is the one-pass selection "first `limit` of x >= ta".
-template <int G, int NG, bool TWO_LEVEL>
-__device__ __forceinline__ void compact_row(const float (&x)[G * NG], int lane, float ta, float tb, int limit,
-                                            int need_b, uint2* stage) {
+// Selecting stage, one level: the candidates are the set bits of m[] (element e of lane l is bit l
+// of m[e]); the first `limit` of them in column order (g, lane, c) are written as (value, column)
+// pairs to stage[0 ..).  CUT = false promises that there are at most `limit` candidates.
+template <int G, int NG, bool CUT>
+__device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const uint64_t (&m)[G * NG], int lane,
+                                              int limit, uint32_t stage_addr) {
+  uint32_t base = 0;  // wave-uniform: candidates in earlier groups
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    uint32_t pos = base;
+#pragma unroll
+    for (int c = 0; c < G; ++c) pos = lanes_below(m[g * G + c], pos);
+#pragma unroll
+    for (int c = 0; c < G; ++c) {
+      const int e = g * G + c;
+      uint64_t mk = m[e];
+      if constexpr (CUT) mk &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
+      lds_store_pair_masked(mk, stage_addr + pos * 8u, __float_as_uint(x[e]), (uint32_t)((g * kWave + lane) * G + c));
+      if (c + 1 < G) pos = add_mask_bit(pos, m[e]);
+    }
+    if (g + 1 < NG) {
+#pragma unroll
+      for (int c = 0; c < G; ++c) base += (uint32_t)__builtin_popcountll(m[g * G + c]);
+    }
+  }
+}
+
+// Selecting stage, two levels (only after the exact search has converged without cnt == k).
+// Class A: x >= ta.  Class B: tb <= x < ta.  All of A is wanted first (cut at `limit` in column
+// order), then the first `need_b` members of B in column order.
+template <int G, int NG>
+__device__ __forceinline__ void compact_two_level(const float (&x)[G * NG], int lane, float ta, float tb, int limit,
+                                                  int need_b, uint2* stage) {
   uint32_t base = 0;    // wave-uniform: chosen elements in earlier groups
   uint32_t base_b = 0;  // wave-uniform: class-B elements in earlier groups
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
-    bool p[G];
-    if constexpr (TWO_LEVEL) {
-      bool b[G];
-      uint64_t mb[G];
-      uint32_t pos_b = base_b;
+    bool p[G], b[G];
+    uint64_t mb[G];
+    uint32_t pos_b = base_b;
 #pragma unroll
-      for (int c = 0; c < G; ++c) {
-        const float v = x[g * G + c];
-        p[c] = v >= ta;
-        b[c] = (v >= tb) && !p[c];
-        mb[c] = __builtin_amdgcn_ballot_w64(b[c]);
-        pos_b = lanes_below(mb[c], pos_b);
-      }
+    for (int c = 0; c < G; ++c) {
+      const float v = x[g * G + c];
+      p[c] = v >= ta;
+      b[c] = (v >= tb) && !p[c];
+      mb[c] = __builtin_amdgcn_ballot_w64(b[c]);
+      pos_b = lanes_below(mb[c], pos_b);
+    }
 #pragma unroll
-      for (int c = 0; c < G; ++c) {
-        p[c] = p[c] || (b[c] && pos_b < (uint32_t)need_b);
-        pos_b += b[c] ? 1u : 0u;
-        base_b += (uint32_t)__builtin_popcountll(mb[c]);
-      }
-    } else {
-#pragma unroll
-      for (int c = 0; c < G; ++c) p[c] = x[g * G + c] >= ta;
+    for (int c = 0; c < G; ++c) {
+      p[c] = p[c] || (b[c] && pos_b < (uint32_t)need_b);
+      pos_b += b[c] ? 1u : 0u;
+      base_b += (uint32_t)__builtin_popcountll(mb[c]);
     }
     uint32_t pos = base;
     uint64_t mk[G];
@@ -136,61 +195,84 @@ template <int G, int NG, bool FULL, bool EXACT>
 __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, int M, int k, int max_iter,
                                            uint2* stage) {
   constexpr int E = G * NG;
-  const float kInf = __builtin_inff();
+  const uint32_t stage_addr = (uint32_t)(uintptr_t)stage;  // LDS byte address
 
   // Alg. 1 / Alg. 2, first two steps: row minimum and maximum.
-  float mx = x[0];
-  float mn = (FULL || lane * G < M) ? x[0] : kInf;
+  float mx, nm;
+  {
+    auto for_min = [&](int e) {  // padding columns must not win the minimum
+      const bool valid = FULL || ((e / G) * kWave + lane) * G < M;
+      return valid ? x[e] : __builtin_inff();
+    };
+    if constexpr (E == 1) {
+      mx = x[0];
+      nm = -for_min(0);
+    } else {
+      mx = vmax(x[0], x[1]);
+      nm = vmax_nn(for_min(0), for_min(1));
 #pragma unroll
-  for (int e = 1; e < E; ++e) {
-    mx = vmax(mx, x[e]);
-    const bool valid = FULL || ((e / G) * kWave + lane) * G < M;
-    mn = vmin(mn, valid ? x[e] : kInf);
+      for (int e = 2; e < E; ++e) {
+        mx = vmax(mx, x[e]);
+        nm = vmax_an(nm, for_min(e));
+      }
+    }
   }
-  float lo = wave_reduce<false>(mn);
-  float hi = wave_reduce<true>(mx);
+  float lo, hi;
+  wave_max_and_negmin(mx, nm, hi, lo);
 
+  uint64_t m[E];
   if constexpr (EXACT) {
-    // The loop ends on cnt == k, or when the fp32 midpoint is no longer strictly inside (lo, hi):
-    // then no representable threshold separates the remaining candidates.
-    float thres = lo;
+    // The loop ends on cnt == k, or once the fp32 midpoint stops changing: then no representable
+    // threshold lies strictly inside (lo, hi).  The latter is tested every second step against the
+    // midpoint of two steps before (a converged search repeats its midpoint for ever, a live one
+    // never returns to an earlier midpoint); the extra steps leave lo and hi untouched.
+    float thres;
+    float seen = lo;
     bool hit = false;
     for (;;) {
       thres = (lo + hi) * 0.5f;
-      if (!(thres > lo && thres < hi)) break;
-      const int cnt = count_ge<E>(x, thres);
+      if (!(thres < seen || thres > seen)) break;
+      seen = thres;
+      int cnt = count_ge<E>(x, thres, m);
       if (cnt == k) {
         hit = true;
         break;
       }
-      if (cnt < k) {
-        hi = thres;
-      } else {
-        lo = thres;
+      move_bound(lo, hi, thres, cnt, k);
+      thres = (lo + hi) * 0.5f;
+      cnt = count_ge<E>(x, thres, m);
+      if (cnt == k) {
+        hit = true;
+        break;
       }
+      move_bound(lo, hi, thres, cnt, k);
     }
     if (hit) {
-      compact_row<G, NG, false>(x, lane, thres, thres, k, 0, stage);
+      compact_masks<G, NG, false>(x, m, lane, k, stage_addr);
     } else {
       // Everything >= hi is in the answer (fewer than k of them unless hi is still the row maximum,
       // in which case they are all equal); the rest comes from [lo, hi) by ascending column.
-      const int na = count_ge<E>(x, hi);
-      compact_row<G, NG, true>(x, lane, hi, lo, k, k - (na < k ? na : k), stage);
+      const int na = count_ge<E>(x, hi, m);
+      compact_two_level<G, NG>(x, lane, hi, lo, k, k - (na < k ? na : k), stage);
     }
   } else {
+    int cnt = -1;
+    bool m_is_for_lo = false;
     for (int it = 0; it < max_iter; ++it) {
       const float thres = (lo + hi) * 0.5f;
-      const int cnt = count_ge<E>(x, thres);
-      if (cnt < k) {
-        hi = thres;
-      } else {
-        lo = thres;
-        // cnt == k: lo can from now on only move to thresholds that still count exactly k, so the
-        // selection is already final.
-        if (cnt == k) break;
-      }
+      cnt = count_ge<E>(x, thres, m);
+      m_is_for_lo = cnt >= k;
+      // cnt == k: lo can from now on only move to thresholds that still count exactly k, so the
+      // selection is already final.
+      if (cnt == k) break;
+      move_bound(lo, hi, thres, cnt, k);
     }
-    compact_row<G, NG, false>(x, lane, lo, lo, k, 0, stage);
+    if (!m_is_for_lo) cnt = count_ge<E>(x, lo, m);
+    if (cnt == k) {
+      compact_masks<G, NG, false>(x, m, lane, k, stage_addr);
+    } else {
+      compact_masks<G, NG, true>(x, m, lane, k, stage_addr);
+    }
   }
 }
 
