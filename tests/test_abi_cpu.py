@@ -1,0 +1,78 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2409_00822_amd as R
+
+    if not os.path.exists(R.lib_path()):
+        from paper_2409_00822_amd import build
+
+        build.build()
+    return R.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rtopk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rtopk_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"rtopk_rowwise", "rtopk_rowwise_exact", "rtopk_rowwise_u8", "rtopk_rowwise_exact_u8",
+            "rtopk_status_string", "rtopk_version", "rtopk_max_m"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_limits_and_status_strings(lib):
+    assert lib.rtopk_version() >= 100
+    assert lib.rtopk_max_m() == 4096
+    seen = set()
+    for code in range(0, -8, -1):
+        s = lib.rtopk_status_string(code)
+        assert s and s != b"unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert lib.rtopk_status_string(-99) == b"unknown status"
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    p = 4096  # a non-null, aligned, never dereferenced "device pointer"
+    f = lib.rtopk_rowwise
+    fe = lib.rtopk_rowwise_exact
+    assert f(p, 0, 256, 32, 8, p, p, None) == 0            # N == 0: nothing to do
+    assert f(None, 0, 256, 32, 8, None, None, None) == 0   # ... even with null pointers
+    assert f(None, 4, 256, 32, 8, p, p, None) == -1
+    assert f(p, 4, 256, 32, 8, None, p, None) == -1
+    assert f(p, 4, 256, 32, 8, p, None, None) == -1
+    assert f(p, -1, 256, 32, 8, p, p, None) == -2
+    assert f(p, 4, 0, 1, 8, p, p, None) == -2
+    assert f(p, 4, 256, 0, 8, p, p, None) == -2
+    assert f(p, 4, 256, 257, 8, p, p, None) == -2
+    assert f(p, 4, 256, 32, -1, p, p, None) == -3
+    assert f(p, 4, 4100, 32, 8, p, p, None) == -4
+    assert fe(p, 4, 4100, 32, p, p, None) == -4
+    assert lib.rtopk_rowwise_u8(p, 4, 260, 32, 8, p, p, None) == -4
+    assert lib.rtopk_rowwise_exact_u8(p, 4, 260, 32, p, p, None) == -4
+    assert f(p + 2, 4, 256, 32, 8, p, p, None) == -5
+    assert f(p, 4, 256, 32, 8, p + 1, p, None) == -5
+    assert f(p, 4, 256, 32, 8, p, p + 2, None) == -5
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+
+    import paper_2409_00822_amd as R
+
+    with pytest.raises(ValueError):
+        R.rtopk_rowwise_exact(torch.zeros(4, 8), 2)
