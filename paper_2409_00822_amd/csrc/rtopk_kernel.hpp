@@ -189,6 +189,94 @@ __device__ __forceinline__ void compact_two_level(const float (&x)[G * NG], int 
   }
 }
 
+// Hand-scheduled search loops for four elements per lane (M <= 256 with 128-bit loads).  Same steps
+// as the generic loops below; written out so that each step costs 9-10 vector and 9-10 scalar
+// instructions.  Masks of the last evaluated threshold come back in m[0..3].
+#define RTOPK_COUNT4                                                     \
+  "v_cmp_ge_f32 %[m0], %[x0], %[t]\n\t"                                   \
+  "v_cmp_ge_f32 %[m1], %[x1], %[t]\n\t"                                   \
+  "v_cmp_ge_f32 %[m2], %[x2], %[t]\n\t"                                   \
+  "v_cmp_ge_f32 %[m3], %[x3], %[t]\n\t"                                   \
+  "s_bcnt1_i32_b64 %[c0], %[m0]\n\t"                                      \
+  "s_bcnt1_i32_b64 %[c1], %[m1]\n\t"                                      \
+  "s_bcnt1_i32_b64 %[c2], %[m2]\n\t"                                      \
+  "s_bcnt1_i32_b64 %[c3], %[m3]\n\t"                                      \
+  "s_add_i32 %[c0], %[c0], %[c1]\n\t"                                     \
+  "s_add_i32 %[c2], %[c2], %[c3]\n\t"                                     \
+  "s_add_i32 %[c0], %[c0], %[c2]\n\t"
+#define RTOPK_MOVE_BOUND                                                 \
+  "v_cmp_lt_i32 vcc, %[c0], %[kv]\n\t"                                    \
+  "v_cndmask_b32 %[hi], %[hi], %[t], vcc\n\t"                             \
+  "v_cndmask_b32 %[lo], %[t], %[lo], vcc\n\t"
+
+// Algorithm 1 at epsilon = 0.  Returns true when a step counted exactly k (m[] then selects the
+// answer); false when the search converged first (lo, hi hold the final bounds).
+__device__ __forceinline__ bool search_exact4(const float (&x)[4], float& lo, float& hi, int k, uint64_t (&m)[4]) {
+  float t, seen;
+  int kv, c0, c1, c2, c3, hit;
+  asm volatile(
+      "v_mov_b32 %[seen], %[lo]\n\t"
+      "v_mov_b32 %[kv], %[k]\n\t"
+      ".Lrtopk_top_%=:\n\t"
+      "v_add_f32 %[t], %[lo], %[hi]\n\t"
+      "v_mul_f32 %[t], 0.5, %[t]\n\t"
+      "v_cmp_lg_f32 vcc, %[t], %[seen]\n\t"
+      "s_cbranch_vccz .Lrtopk_conv_%=\n\t"
+      "v_mov_b32 %[seen], %[t]\n\t"
+      RTOPK_COUNT4
+      "s_cmp_eq_u32 %[c0], %[k]\n\t"
+      "s_cbranch_scc1 .Lrtopk_hit_%=\n\t"
+      RTOPK_MOVE_BOUND
+      "v_add_f32 %[t], %[lo], %[hi]\n\t"
+      "v_mul_f32 %[t], 0.5, %[t]\n\t"
+      RTOPK_COUNT4
+      "s_cmp_eq_u32 %[c0], %[k]\n\t"
+      "s_cbranch_scc1 .Lrtopk_hit_%=\n\t"
+      RTOPK_MOVE_BOUND
+      "s_branch .Lrtopk_top_%=\n\t"
+      ".Lrtopk_conv_%=:\n\t"
+      "s_mov_b32 %[hit], 0\n\t"
+      "s_branch .Lrtopk_end_%=\n\t"
+      ".Lrtopk_hit_%=:\n\t"
+      "s_mov_b32 %[hit], 1\n\t"
+      ".Lrtopk_end_%=:"
+      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [seen] "=&v"(seen), [kv] "=&v"(kv), [m0] "=&s"(m[0]),
+        [m1] "=&s"(m[1]), [m2] "=&s"(m[2]), [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2),
+        [c3] "=&s"(c3), [hit] "=&s"(hit)
+      : [x0] "v"(x[0]), [x1] "v"(x[1]), [x2] "v"(x[2]), [x3] "v"(x[3]), [k] "s"(k)
+      : "vcc", "scc");
+  return hit != 0;
+}
+
+// Algorithm 2: max_iter steps (fewer when a step counts exactly k).  Returns the count of the last
+// step, or -1 when no step ran; when it is >= k, m[] holds the masks of x >= lo.
+__device__ __forceinline__ int search_early4(const float (&x)[4], float& lo, float& hi, int k, int max_iter,
+                                             uint64_t (&m)[4]) {
+  float t;
+  int kv, c0, c1, c2, c3, it;
+  asm volatile(
+      "v_mov_b32 %[kv], %[k]\n\t"
+      "s_mov_b32 %[c0], -1\n\t"
+      "s_sub_u32 %[it], %[n], 1\n\t"
+      "s_cbranch_scc1 .Lrtopk_end_%=\n\t"
+      ".Lrtopk_top_%=:\n\t"
+      "v_add_f32 %[t], %[lo], %[hi]\n\t"
+      "v_mul_f32 %[t], 0.5, %[t]\n\t"
+      RTOPK_COUNT4
+      RTOPK_MOVE_BOUND
+      "s_cmp_eq_u32 %[c0], %[k]\n\t"
+      "s_cbranch_scc1 .Lrtopk_end_%=\n\t"
+      "s_sub_u32 %[it], %[it], 1\n\t"
+      "s_cbranch_scc0 .Lrtopk_top_%=\n\t"
+      ".Lrtopk_end_%=:"
+      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [kv] "=&v"(kv), [m0] "=&s"(m[0]), [m1] "=&s"(m[1]),
+        [m2] "=&s"(m[2]), [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3),
+        [it] "=&s"(it)
+      : [x0] "v"(x[0]), [x1] "v"(x[1]), [x2] "v"(x[2]), [x3] "v"(x[3]), [k] "s"(k), [n] "s"(max_iter)
+      : "vcc", "scc");
+  return c0;
+}
+
 // Search and selection for one row held as x[E] (columns past M hold -inf and are never chosen).
 //   EXACT: Algorithm 1 at epsilon = 0; otherwise Algorithm 2 with max_iter steps.
 template <int G, int NG, bool FULL, bool EXACT>
@@ -226,26 +314,30 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
     // threshold lies strictly inside (lo, hi).  The latter is tested every second step against the
     // midpoint of two steps before (a converged search repeats its midpoint for ever, a live one
     // never returns to an earlier midpoint); the extra steps leave lo and hi untouched.
-    float thres;
-    float seen = lo;
     bool hit = false;
-    for (;;) {
-      thres = (lo + hi) * 0.5f;
-      if (!(thres < seen || thres > seen)) break;
-      seen = thres;
-      int cnt = count_ge<E>(x, thres, m);
-      if (cnt == k) {
-        hit = true;
-        break;
+    if constexpr (E == 4) {
+      hit = search_exact4(x, lo, hi, k, m);
+    } else {
+      float thres;
+      float seen = lo;
+      for (;;) {
+        thres = (lo + hi) * 0.5f;
+        if (!(thres < seen || thres > seen)) break;
+        seen = thres;
+        int cnt = count_ge<E>(x, thres, m);
+        if (cnt == k) {
+          hit = true;
+          break;
+        }
+        move_bound(lo, hi, thres, cnt, k);
+        thres = (lo + hi) * 0.5f;
+        cnt = count_ge<E>(x, thres, m);
+        if (cnt == k) {
+          hit = true;
+          break;
+        }
+        move_bound(lo, hi, thres, cnt, k);
       }
-      move_bound(lo, hi, thres, cnt, k);
-      thres = (lo + hi) * 0.5f;
-      cnt = count_ge<E>(x, thres, m);
-      if (cnt == k) {
-        hit = true;
-        break;
-      }
-      move_bound(lo, hi, thres, cnt, k);
     }
     if (hit) {
       compact_masks<G, NG, false>(x, m, lane, k, stage_addr);
@@ -257,17 +349,19 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
     }
   } else {
     int cnt = -1;
-    bool m_is_for_lo = false;
-    for (int it = 0; it < max_iter; ++it) {
-      const float thres = (lo + hi) * 0.5f;
-      cnt = count_ge<E>(x, thres, m);
-      m_is_for_lo = cnt >= k;
-      // cnt == k: lo can from now on only move to thresholds that still count exactly k, so the
-      // selection is already final.
-      if (cnt == k) break;
-      move_bound(lo, hi, thres, cnt, k);
+    if constexpr (E == 4) {
+      cnt = search_early4(x, lo, hi, k, max_iter, m);
+    } else {
+      for (int it = 0; it < max_iter; ++it) {
+        const float thres = (lo + hi) * 0.5f;
+        cnt = count_ge<E>(x, thres, m);
+        // cnt == k: lo can from now on only move to thresholds that still count exactly k, so the
+        // selection is already final.
+        if (cnt == k) break;
+        move_bound(lo, hi, thres, cnt, k);
+      }
     }
-    if (!m_is_for_lo) cnt = count_ge<E>(x, lo, m);
+    if (cnt < k) cnt = count_ge<E>(x, lo, m);  // the last step lowered hi (or none ran): m[] is not for lo
     if (cnt == k) {
       compact_masks<G, NG, false>(x, m, lane, k, stage_addr);
     } else {
@@ -292,6 +386,23 @@ template <>
 struct VecOf<4> {
   using type = float4;
 };
+
+// One G-wide load with the non-temporal hint: every input byte is read exactly once, and keeping it
+// out of the caches' retention policy measurably raises the streaming rate.
+template <int G>
+__device__ __forceinline__ typename VecOf<G>::type load_streaming(const float* p) {
+  if constexpr (G == 1) {
+    return __builtin_nontemporal_load(p);
+  } else if constexpr (G == 2) {
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const f2 v = __builtin_nontemporal_load(reinterpret_cast<const f2*>(p));
+    return make_float2(v.x, v.y);
+  } else {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+  }
+}
 
 template <int G, int NG, int R, bool FULL, bool EXACT, typename IdxT>
 __global__ void __launch_bounds__(256)
@@ -318,7 +429,7 @@ __global__ void __launch_bounds__(256)
     for (int g = 0; g < NG; ++g) {
       const int col0 = (g * kWave + lane) * G;
       if (FULL || col0 < M) {
-        const V v = *reinterpret_cast<const V*>(row + col0);
+const V v = load_streaming<G>(row + col0);
         if constexpr (G == 1) {
           x[rr][g] = v;
         } else if constexpr (G == 2) {
