@@ -47,6 +47,22 @@ __device__ __forceinline__ float vmax_nn(float a, float b) {  // max(-a, -b) = -
   return r;
 }
 
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float vmax3_nnn(float a, float b, float c) {  // max(-a, -b, -c)
+  float r;
+  asm("v_max3_f32 %0, -%1, -%2, -%3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float vmax3_ann(float a, float b, float c) {  // max(a, -b, -c)
+  float r;
+  asm("v_max3_f32 %0, %1, -%2, -%3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Row maximum and minimum in one reduction.  On entry every lane holds mx = max of its elements and
 // nm = max of its negated elements.  The two halves of the wavefront are swapped so that lanes 0..31
 // reduce the maxima and lanes 32..63 the negated minima with the same five DPP steps.
@@ -94,6 +110,25 @@ __device__ __forceinline__ void lds_store_pair_masked(uint64_t mask, uint32_t ad
       : "memory");
 }
 
+// The same for four elements at once (one EXEC restore instead of four).
+__device__ __forceinline__ void lds_store_pairs_masked4(const uint64_t (&mk)[4], const uint32_t (&addr)[4],
+                                                        const float (&a)[4], const uint32_t (&b)[4]) {
+  asm volatile(
+      "s_mov_b64 exec, %0\n\t"
+      "ds_write2_b32 %4, %8, %12 offset1:1\n\t"
+      "s_mov_b64 exec, %1\n\t"
+      "ds_write2_b32 %5, %9, %13 offset1:1\n\t"
+      "s_mov_b64 exec, %2\n\t"
+      "ds_write2_b32 %6, %10, %14 offset1:1\n\t"
+      "s_mov_b64 exec, %3\n\t"
+      "ds_write2_b32 %7, %11, %15 offset1:1\n\t"
+      "s_mov_b64 exec, -1"
+      :
+      : "s"(mk[0]), "s"(mk[1]), "s"(mk[2]), "s"(mk[3]), "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3]),
+        "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(b[0]), "v"(b[1]), "v"(b[2]), "v"(b[3])
+      : "memory");
+}
+
 // if (cnt < k) hi = t; else lo = t;   (all operands wave-uniform)
 __device__ __forceinline__ void move_bound(float& lo, float& hi, float t, int cnt, int k) {
   const bool less = cnt < k;
@@ -128,13 +163,31 @@ __device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const ui
     uint32_t pos = base;
 #pragma unroll
     for (int c = 0; c < G; ++c) pos = lanes_below(m[g * G + c], pos);
+    if constexpr (G == 4) {
+      uint64_t mk[4];
+      uint32_t addr[4], col[4];
+      float val[4];
 #pragma unroll
-    for (int c = 0; c < G; ++c) {
-      const int e = g * G + c;
-      uint64_t mk = m[e];
-      if constexpr (CUT) mk &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
-      lds_store_pair_masked(mk, stage_addr + pos * 8u, __float_as_uint(x[e]), (uint32_t)((g * kWave + lane) * G + c));
-      if (c + 1 < G) pos = add_mask_bit(pos, m[e]);
+      for (int c = 0; c < 4; ++c) {
+        const int e = g * 4 + c;
+        mk[c] = m[e];
+        if constexpr (CUT) mk[c] &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
+        addr[c] = stage_addr + pos * 8u;
+        val[c] = x[e];
+        col[c] = (uint32_t)((g * kWave + lane) * 4 + c);
+        if (c + 1 < 4) pos = add_mask_bit(pos, m[e]);
+      }
+      lds_store_pairs_masked4(mk, addr, val, col);
+    } else {
+#pragma unroll
+      for (int c = 0; c < G; ++c) {
+        const int e = g * G + c;
+        uint64_t mk = m[e];
+        if constexpr (CUT) mk &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
+        lds_store_pair_masked(mk, stage_addr + pos * 8u, __float_as_uint(x[e]),
+                              (uint32_t)((g * kWave + lane) * G + c));
+        if (c + 1 < G) pos = add_mask_bit(pos, m[e]);
+      }
     }
     if (g + 1 < NG) {
 #pragma unroll
@@ -190,8 +243,10 @@ __device__ __forceinline__ void compact_two_level(const float (&x)[G * NG], int 
 }
 
 // Hand-scheduled search loops for four elements per lane (M <= 256 with 128-bit loads).  Same steps
-// as the generic loops below; written out so that each step costs 9-10 vector and 9-10 scalar
-// instructions.  Masks of the last evaluated threshold come back in m[0..3].
+// as the generic loops below, written out so that a step costs about 7 vector and 11 scalar
+// instructions: the wave-uniform bounds are moved with one v_mov under a scalar branch.  Masks of the
+// last evaluated threshold come back in m[0..3].
+#define RTOPK_MID "v_add_f32 %[t], %[lo], %[hi]\n\tv_mul_f32 %[t], 0.5, %[t]\n\t"
 #define RTOPK_COUNT4                                                     \
   "v_cmp_ge_f32 %[m0], %[x0], %[t]\n\t"                                   \
   "v_cmp_ge_f32 %[m1], %[x1], %[t]\n\t"                                   \
@@ -204,45 +259,62 @@ __device__ __forceinline__ void compact_two_level(const float (&x)[G * NG], int 
   "s_add_i32 %[c0], %[c0], %[c1]\n\t"                                     \
   "s_add_i32 %[c2], %[c2], %[c3]\n\t"                                     \
   "s_add_i32 %[c0], %[c0], %[c2]\n\t"
-#define RTOPK_MOVE_BOUND                                                 \
-  "v_cmp_lt_i32 vcc, %[c0], %[kv]\n\t"                                    \
-  "v_cndmask_b32 %[hi], %[hi], %[t], vcc\n\t"                             \
-  "v_cndmask_b32 %[lo], %[t], %[lo], vcc\n\t"
 
 // Algorithm 1 at epsilon = 0.  Returns true when a step counted exactly k (m[] then selects the
-// answer); false when the search converged first (lo, hi hold the final bounds).
+// answer); false when the search converged first (lo, hi hold the final bounds).  Steps alternate
+// between two code copies A and B that keep their midpoints in different registers, so that copy A
+// can compare its midpoint with the previous one: equal (or unordered) means converged.
 __device__ __forceinline__ bool search_exact4(const float (&x)[4], float& lo, float& hi, int k, uint64_t (&m)[4]) {
-  float t, seen;
-  int kv, c0, c1, c2, c3, hit;
+  float t, u;
+  int c0, c1, c2, c3, hit;
   asm volatile(
-      "v_mov_b32 %[seen], %[lo]\n\t"
-      "v_mov_b32 %[kv], %[k]\n\t"
-      ".Lrtopk_top_%=:\n\t"
-      "v_add_f32 %[t], %[lo], %[hi]\n\t"
-      "v_mul_f32 %[t], 0.5, %[t]\n\t"
-      "v_cmp_lg_f32 vcc, %[t], %[seen]\n\t"
+      // ---- copy B (entry): midpoint in u, no convergence test
+      ".Lrtopk_b_%=:\n\t"
+      "v_add_f32 %[u], %[lo], %[hi]\n\t"
+      "v_mul_f32 %[u], 0.5, %[u]\n\t"
+      "v_cmp_ge_f32 %[m0], %[x0], %[u]\n\t"
+      "v_cmp_ge_f32 %[m1], %[x1], %[u]\n\t"
+      "v_cmp_ge_f32 %[m2], %[x2], %[u]\n\t"
+      "v_cmp_ge_f32 %[m3], %[x3], %[u]\n\t"
+      "s_bcnt1_i32_b64 %[c0], %[m0]\n\t"
+      "s_bcnt1_i32_b64 %[c1], %[m1]\n\t"
+      "s_bcnt1_i32_b64 %[c2], %[m2]\n\t"
+      "s_bcnt1_i32_b64 %[c3], %[m3]\n\t"
+      "s_add_i32 %[c0], %[c0], %[c1]\n\t"
+      "s_add_i32 %[c2], %[c2], %[c3]\n\t"
+      "s_add_i32 %[c0], %[c0], %[c2]\n\t"
+      "s_cmp_lt_i32 %[c0], %[k]\n\t"
+      "s_cbranch_scc1 .Lrtopk_bless_%=\n\t"
+      "s_cmp_gt_i32 %[c0], %[k]\n\t"
+      "v_mov_b32 %[lo], %[u]\n\t"
+      "s_cbranch_scc1 .Lrtopk_a_%=\n\t"
+      "s_branch .Lrtopk_hit_%=\n\t"
+      ".Lrtopk_bless_%=:\n\t"
+      "v_mov_b32 %[hi], %[u]\n\t"
+      // ---- copy A: midpoint in t, compared with copy B's
+      ".Lrtopk_a_%=:\n\t"
+      RTOPK_MID
+      "v_cmp_lg_f32 vcc, %[t], %[u]\n\t"
       "s_cbranch_vccz .Lrtopk_conv_%=\n\t"
-      "v_mov_b32 %[seen], %[t]\n\t"
       RTOPK_COUNT4
-      "s_cmp_eq_u32 %[c0], %[k]\n\t"
-      "s_cbranch_scc1 .Lrtopk_hit_%=\n\t"
-      RTOPK_MOVE_BOUND
-      "v_add_f32 %[t], %[lo], %[hi]\n\t"
-      "v_mul_f32 %[t], 0.5, %[t]\n\t"
-      RTOPK_COUNT4
-      "s_cmp_eq_u32 %[c0], %[k]\n\t"
-      "s_cbranch_scc1 .Lrtopk_hit_%=\n\t"
-      RTOPK_MOVE_BOUND
-      "s_branch .Lrtopk_top_%=\n\t"
+      "s_cmp_lt_i32 %[c0], %[k]\n\t"
+      "s_cbranch_scc1 .Lrtopk_aless_%=\n\t"
+      "s_cmp_gt_i32 %[c0], %[k]\n\t"
+      "v_mov_b32 %[lo], %[t]\n\t"
+      "s_cbranch_scc1 .Lrtopk_b_%=\n\t"
+      "s_branch .Lrtopk_hit_%=\n\t"
+      ".Lrtopk_aless_%=:\n\t"
+      "v_mov_b32 %[hi], %[t]\n\t"
+      "s_branch .Lrtopk_b_%=\n\t"
       ".Lrtopk_conv_%=:\n\t"
       "s_mov_b32 %[hit], 0\n\t"
       "s_branch .Lrtopk_end_%=\n\t"
       ".Lrtopk_hit_%=:\n\t"
       "s_mov_b32 %[hit], 1\n\t"
       ".Lrtopk_end_%=:"
-      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [seen] "=&v"(seen), [kv] "=&v"(kv), [m0] "=&s"(m[0]),
-        [m1] "=&s"(m[1]), [m2] "=&s"(m[2]), [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2),
-        [c3] "=&s"(c3), [hit] "=&s"(hit)
+      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [u] "=&v"(u), [m0] "=&s"(m[0]), [m1] "=&s"(m[1]),
+        [m2] "=&s"(m[2]), [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3),
+        [hit] "=&s"(hit)
       : [x0] "v"(x[0]), [x1] "v"(x[1]), [x2] "v"(x[2]), [x3] "v"(x[3]), [k] "s"(k)
       : "vcc", "scc");
   return hit != 0;
@@ -253,25 +325,29 @@ __device__ __forceinline__ bool search_exact4(const float (&x)[4], float& lo, fl
 __device__ __forceinline__ int search_early4(const float (&x)[4], float& lo, float& hi, int k, int max_iter,
                                              uint64_t (&m)[4]) {
   float t;
-  int kv, c0, c1, c2, c3, it;
+  int c0, c1, c2, c3, it;
   asm volatile(
-      "v_mov_b32 %[kv], %[k]\n\t"
       "s_mov_b32 %[c0], -1\n\t"
       "s_sub_u32 %[it], %[n], 1\n\t"
       "s_cbranch_scc1 .Lrtopk_end_%=\n\t"
       ".Lrtopk_top_%=:\n\t"
-      "v_add_f32 %[t], %[lo], %[hi]\n\t"
-      "v_mul_f32 %[t], 0.5, %[t]\n\t"
+      RTOPK_MID
       RTOPK_COUNT4
-      RTOPK_MOVE_BOUND
-      "s_cmp_eq_u32 %[c0], %[k]\n\t"
-      "s_cbranch_scc1 .Lrtopk_end_%=\n\t"
+      "s_cmp_lt_i32 %[c0], %[k]\n\t"
+      "s_cbranch_scc1 .Lrtopk_less_%=\n\t"
+      "s_cmp_gt_i32 %[c0], %[k]\n\t"
+      "v_mov_b32 %[lo], %[t]\n\t"
+      "s_cbranch_scc0 .Lrtopk_end_%=\n\t"
+      "s_sub_u32 %[it], %[it], 1\n\t"
+      "s_cbranch_scc0 .Lrtopk_top_%=\n\t"
+      "s_branch .Lrtopk_end_%=\n\t"
+      ".Lrtopk_less_%=:\n\t"
+      "v_mov_b32 %[hi], %[t]\n\t"
       "s_sub_u32 %[it], %[it], 1\n\t"
       "s_cbranch_scc0 .Lrtopk_top_%=\n\t"
       ".Lrtopk_end_%=:"
-      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [kv] "=&v"(kv), [m0] "=&s"(m[0]), [m1] "=&s"(m[1]),
-        [m2] "=&s"(m[2]), [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3),
-        [it] "=&s"(it)
+      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [m0] "=&s"(m[0]), [m1] "=&s"(m[1]), [m2] "=&s"(m[2]),
+        [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3), [it] "=&s"(it)
       : [x0] "v"(x[0]), [x1] "v"(x[1]), [x2] "v"(x[2]), [x3] "v"(x[3]), [k] "s"(k), [n] "s"(max_iter)
       : "vcc", "scc");
   return c0;
@@ -295,11 +371,19 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
     if constexpr (E == 1) {
       mx = x[0];
       nm = -for_min(0);
-    } else {
+    } else if constexpr (E == 2) {
       mx = vmax(x[0], x[1]);
       nm = vmax_nn(for_min(0), for_min(1));
+    } else {
+      mx = vmax3(x[0], x[1], x[2]);
+      nm = vmax3_nnn(for_min(0), for_min(1), for_min(2));
+      int e = 3;
 #pragma unroll
-      for (int e = 2; e < E; ++e) {
+      for (; e + 1 < E; e += 2) {
+        mx = vmax3(mx, x[e], x[e + 1]);
+        nm = vmax3_ann(nm, for_min(e), for_min(e + 1));
+      }
+      if (e < E) {
         mx = vmax(mx, x[e]);
         nm = vmax_an(nm, for_min(e));
       }
