@@ -19,6 +19,9 @@ import sys
 import time
 
 PEAK_HBM_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the exact kernel at the headline shape, from the rocprofv3 --pmc runs summarised
+# in profiles/rtopk_wave_kernel_c1_maxk_pmc.md (not measured live: counters need the profiler).
+MEASURED_TRAFFIC_BYTES = 1342370645
 
 
 def log(*a):
@@ -26,22 +29,26 @@ def log(*a):
 
 
 def time_calls(torch, fn, steps, warmup):
-    """Returns (wall seconds for `steps` calls, mean per-launch seconds from HIP events)."""
+    """Returns (wall seconds for `steps` calls, mean seconds per launch).
+
+    Wall time is taken between two device synchronisations.  The per-launch figure comes from one pair
+    of HIP events recorded on the launch stream right before the first and right after the last of the
+    `steps` back-to-back launches (so it is the steady-state launch-to-launch duration on the GPU's own
+    clock, without the host's synchronisation cost)."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    start = torch.cuda.Event(enable_timing=True)
+    end = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
-        starts[i].record()
+    start.record()
+    for _ in range(steps):
         fn()
-        ends[i].record()
+    end.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per = [s.elapsed_time(e) * 1e-3 for s, e in zip(starts, ends)]
-    return wall, sum(per) / len(per), per
+    return wall, start.elapsed_time(end) * 1e-3 / steps
 
 
 def main():
@@ -91,10 +98,10 @@ def main():
         R.rtopk_rowwise(x, k, max_iter, out_v, out_i)
 
     log("timing exact mode ...")
-    wall_e, launch_e, _ = time_calls(torch, exact, args.steps, args.warmup)
+    wall_e, launch_e = time_calls(torch, exact, args.steps, args.warmup)
     log(f"  exact: {wall_e / args.steps * 1e6:.1f} us/step wall, {launch_e * 1e6:.1f} us/launch (events)")
     log(f"timing early-stop mode (max_iter={max_iter}) ...")
-    wall_s, launch_s, _ = time_calls(torch, early, args.steps, args.warmup)
+    wall_s, launch_s = time_calls(torch, early, args.steps, args.warmup)
     log(f"  early: {wall_s / args.steps * 1e6:.1f} us/step wall, {launch_s * 1e6:.1f} us/launch (events)")
 
     if args.with_copy:
@@ -157,9 +164,11 @@ def main():
                        "hbm_gbps": algo_bytes / launch_s / 1e9, "recall_vs_exact": recall},
         "parity_vs_oracle": parity,
         "roofline": {"bound": "hbm", "achieved": algo_bytes / launch_e / 1e9, "peak": PEAK_HBM_GBPS,
-                     "unit": "GB/s", "frac": algo_bytes / launch_e / 1e9 / PEAK_HBM_GBPS, "traffic": None,
-                     "kernel": "rtopk_wave_kernel<G=4,NG=1,exact,int32>", "algorithmic_bytes_per_launch": algo_bytes,
-                     "avg_launch_us": launch_e * 1e6},
+                     "unit": "GB/s", "frac": algo_bytes / launch_e / 1e9 / PEAK_HBM_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES if (N, k) == (1 << 20, 32) else None,
+                     "traffic_source": "profiles/rtopk_wave_kernel_c1_maxk_pmc.md (FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
+                     "kernel": "rtopk_wave_kernel<G=4,NG=1,R=8,full,exact,int32>",
+                     "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": launch_e * 1e6},
         "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
