@@ -56,8 +56,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--rows", type=int, default=1 << 20, help="N (default: the headline 2^20)")
-    ap.add_argument("--k", type=int, default=32)
+    ap.add_argument("--workload", default="c1_maxk",
+                    help="name in workloads.CONFIGS (default: the headline c1_maxk, N=2^20 x M=256)")
+    ap.add_argument("--rows", type=int, default=None, help="override the workload's N")
+    ap.add_argument("--k", type=int, default=None, help="default: 32 for M=256, else the workload's first k")
     ap.add_argument("--max-iter", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
@@ -81,21 +83,28 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(1)
 
-    N, M, k, max_iter = args.rows, 256, args.k, args.max_iter
-    log(f"generating c1_maxk input N={N} M={M} ...")
-    x_host = workloads.make("c1_maxk", N=N)
+    cfg = workloads.CONFIGS[args.workload]
+    N = args.rows if args.rows is not None else cfg["N"]
+    M, max_iter = cfg["M"], args.max_iter
+    k = args.k if args.k is not None else (32 if 32 in cfg["ks"] else cfg["ks"][0])
+    u8 = cfg["idx"] == "uint8"
+    log(f"generating {args.workload} input N={N} M={M} ...")
+    x_host = workloads.make(args.workload, N=N)
     x = torch.from_numpy(x_host).cuda()
     out_v = torch.empty((N, k), dtype=torch.float32, device="cuda")
-    out_i = torch.empty((N, k), dtype=torch.int32, device="cuda")
+    out_i = torch.empty((N, k), dtype=torch.uint8 if u8 else torch.int32, device="cuda")
     torch.cuda.synchronize()
 
-    algo_bytes = N * (4 * M + k * (4 + 4))  # read the row once, write k (value, int32 column) pairs once
+    # read the row once, write k (value, column) pairs once
+    algo_bytes = N * (4 * M + k * (4 + (1 if u8 else 4)))
+    f_exact = R.rtopk_rowwise_exact_u8 if u8 else R.rtopk_rowwise_exact
+    f_early = R.rtopk_rowwise_u8 if u8 else R.rtopk_rowwise
 
     def exact():
-        R.rtopk_rowwise_exact(x, k, out_v, out_i)
+        f_exact(x, k, out_v, out_i)
 
     def early():
-        R.rtopk_rowwise(x, k, max_iter, out_v, out_i)
+        f_early(x, k, max_iter, out_v, out_i)
 
     log("timing exact mode ...")
     wall_e, launch_e = time_calls(torch, exact, args.steps, args.warmup)
@@ -121,12 +130,12 @@ def main():
         ev, ei = oracle.topk_exact(x_host, k)
         exact()
         torch.cuda.synchronize()
-        ok_e = bool(np.array_equal(out_i.cpu().numpy(), ei)
+        ok_e = bool(np.array_equal(out_i.cpu().numpy().astype(np.int32), ei)
                     and np.array_equal(out_v.cpu().numpy().view(np.int32), ev.view(np.int32)))
         sv, si = oracle.topk_earlystop(x_host, k, max_iter)
         early()
         torch.cuda.synchronize()
-        gi = out_i.cpu().numpy()
+        gi = out_i.cpu().numpy().astype(np.int32)
         ok_s = bool(np.array_equal(gi, si) and np.array_equal(out_v.cpu().numpy().view(np.int32), sv.view(np.int32)))
         parity = {"exact": ok_e, "early_stop": ok_s}
         recall = oracle.mean_overlap(gi, ei)
@@ -145,7 +154,7 @@ def main():
 
     rows_per_s = N * args.steps / wall_e
     result = {
-        "metric": "rows/sec, row top-k N=2^20 M=256 k=32 fp32, exact mode (early-stop alongside)",
+        "metric": "rows/sec, row top-k N=%d M=%d k=%d fp32, exact mode (early-stop alongside)" % (N, M, k),
         "value": rows_per_s,
         "unit": "rows/s",
         "n_gpus": 1,
@@ -157,17 +166,17 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "c1_maxk: N=%d x M=256 fp32, rows ~ s_r*N(0,1), s_r~U(0.5,2), seed 1" % N,
-                   "k": k, "mode": "exact", "index_type": "int32"},
+        "config": {"workload": "%s: N=%d x M=%d fp32, %s, seed %d" % (args.workload, N, M, cfg["dist"], cfg["seed"]),
+                   "k": k, "mode": "exact", "index_type": cfg["idx"]},
         "early_stop": {"max_iter": max_iter, "rows_per_s": N * args.steps / wall_s,
                        "ms_per_step": wall_s / args.steps * 1e3,
                        "hbm_gbps": algo_bytes / launch_s / 1e9, "recall_vs_exact": recall},
         "parity_vs_oracle": parity,
         "roofline": {"bound": "hbm", "achieved": algo_bytes / launch_e / 1e9, "peak": PEAK_HBM_GBPS,
                      "unit": "GB/s", "frac": algo_bytes / launch_e / 1e9 / PEAK_HBM_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES if (N, k) == (1 << 20, 32) else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES if (args.workload, N, k) == ("c1_maxk", 1 << 20, 32) else None,
                      "traffic_source": "profiles/rtopk_wave_kernel_c1_maxk_pmc.md (FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
-                     "kernel": "rtopk_wave_kernel<G=4,NG=1,R=8,full,exact,int32>",
+                     "kernel": "rtopk_wave_kernel, exact mode, M=%d" % M,
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": launch_e * 1e6},
         "cpu_baseline": cpu,
     }

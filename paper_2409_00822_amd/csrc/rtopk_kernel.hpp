@@ -151,95 +151,132 @@ __device__ __forceinline__ int count_ge(const float (&x)[E], float t, uint64_t (
   return cnt;
 }
 
+// Sum of a per-lane integer over the wavefront (result wave-uniform).
+__device__ __forceinline__ int wave_sum(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false);  // row_half_mirror
+  v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, false);  // row_mirror
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+  return __builtin_amdgcn_readlane(v, 63);
+}
+
+// The same count for wide rows, without keeping masks.  A mask popcount costs one vector and two
+// scalar instructions per 64 elements, a per-lane accumulation two vector and no scalar ones; wide
+// rows split the elements between the two so that neither unit is the bottleneck (ACC of the E
+// elements are accumulated per lane and reduced once).
+template <int E, int ACC>
+__device__ __forceinline__ int count_ge_wide(const float (&x)[E], float t) {
+  int cnt = 0;
+#pragma unroll
+  for (int e = ACC; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= t));
+  if constexpr (ACC > 0) {
+    int acc = 0;
+#pragma unroll
+    for (int e = 0; e < ACC; ++e) acc += (x[e] >= t) ? 1 : 0;
+    cnt += wave_sum(acc);
+  }
+  return cnt;
+}
+
 // Selecting stage, one level: the candidates are the set bits of m[] (element e of lane l is bit l
 // of m[e]); the first `limit` of them in column order (g, lane, c) are written as (value, column)
 // pairs to stage[0 ..).  CUT = false promises that there are at most `limit` candidates.
-template <int G, int NG, bool CUT>
-__device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const uint64_t (&m)[G * NG], int lane,
-                                              int limit, uint32_t stage_addr) {
+// LAZY: the masks are not passed in but formed here, group by group, as x >= t, where t is `t_hi`
+// for columns above `split_col` and `t_lo` for columns up to it (a plain threshold has t_lo == t_hi).
+template <int G, int NG, bool CUT, bool LAZY = false>
+__device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const uint64_t* mm, float t_hi, float t_lo,
+                                              int split_col, int lane, int limit, uint32_t stage_addr) {
   uint32_t base = 0;  // wave-uniform: candidates in earlier groups
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
+    // An opaque copy of the lane id per group: otherwise the column numbers of all groups, shared by
+    // every call site, are computed up front and stay live through the whole search.
+    int ln = lane;
+    if constexpr (NG > 4) asm volatile("" : "+v"(ln));
+    uint64_t m[G];
+#pragma unroll
+    for (int c = 0; c < G; ++c) {
+      if constexpr (LAZY) {
+        const int col = (g * kWave + ln) * G + c;
+        m[c] = __builtin_amdgcn_ballot_w64(x[g * G + c] >= (col <= split_col ? t_lo : t_hi));
+      } else {
+        m[c] = mm[g * G + c];
+      }
+    }
     uint32_t pos = base;
 #pragma unroll
-    for (int c = 0; c < G; ++c) pos = lanes_below(m[g * G + c], pos);
+    for (int c = 0; c < G; ++c) pos = lanes_below(m[c], pos);
     if constexpr (G == 4) {
       uint64_t mk[4];
       uint32_t addr[4], col[4];
       float val[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const int e = g * 4 + c;
-        mk[c] = m[e];
+        mk[c] = m[c];
         if constexpr (CUT) mk[c] &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
         addr[c] = stage_addr + pos * 8u;
-        val[c] = x[e];
-        col[c] = (uint32_t)((g * kWave + lane) * 4 + c);
-        if (c + 1 < 4) pos = add_mask_bit(pos, m[e]);
+        val[c] = x[g * 4 + c];
+        col[c] = (uint32_t)((g * kWave + ln) * 4 + c);
+        if (c + 1 < 4) pos = add_mask_bit(pos, m[c]);
       }
       lds_store_pairs_masked4(mk, addr, val, col);
     } else {
 #pragma unroll
       for (int c = 0; c < G; ++c) {
-        const int e = g * G + c;
-        uint64_t mk = m[e];
+        uint64_t mk = m[c];
         if constexpr (CUT) mk &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
-        lds_store_pair_masked(mk, stage_addr + pos * 8u, __float_as_uint(x[e]),
-                              (uint32_t)((g * kWave + lane) * G + c));
-        if (c + 1 < G) pos = add_mask_bit(pos, m[e]);
+        lds_store_pair_masked(mk, stage_addr + pos * 8u, __float_as_uint(x[g * G + c]),
+                              (uint32_t)((g * kWave + ln) * G + c));
+        if (c + 1 < G) pos = add_mask_bit(pos, m[c]);
       }
     }
     if (g + 1 < NG) {
 #pragma unroll
-      for (int c = 0; c < G; ++c) base += (uint32_t)__builtin_popcountll(m[g * G + c]);
+      for (int c = 0; c < G; ++c) base += (uint32_t)__builtin_popcountll(m[c]);
     }
+    // keep the groups in program order: hoisting every group's compares would hold all masks live
+    if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-// Selecting stage, two levels (only after the exact search has converged without cnt == k).
-// Class A: x >= ta.  Class B: tb <= x < ta.  All of A is wanted first (cut at `limit` in column
-// order), then the first `need_b` members of B in column order.
+// Column of the `want`-th (1-based) element, in column order, among those with tb <= x < ta;
+// -1 when want == 0.  Used only after the exact search has converged without cnt == k.
 template <int G, int NG>
-__device__ __forceinline__ void compact_two_level(const float (&x)[G * NG], int lane, float ta, float tb, int limit,
-                                                  int need_b, uint2* stage) {
-  uint32_t base = 0;    // wave-uniform: chosen elements in earlier groups
-  uint32_t base_b = 0;  // wave-uniform: class-B elements in earlier groups
+__device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int lane, float ta, float tb, int want) {
+  uint32_t base = 0;  // wave-uniform: band members in earlier groups
+  int mine = -1;      // per lane: the wanted column if this lane owns it
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
-    bool p[G], b[G];
-    uint64_t mb[G];
-    uint32_t pos_b = base_b;
+    int ln = lane;  // opaque per group, see compact_masks
+    if constexpr (NG > 4) asm volatile("" : "+v"(ln));
+    uint32_t pos = base;
+    bool b[G];
 #pragma unroll
     for (int c = 0; c < G; ++c) {
       const float v = x[g * G + c];
-      p[c] = v >= ta;
-      b[c] = (v >= tb) && !p[c];
-      mb[c] = __builtin_amdgcn_ballot_w64(b[c]);
-      pos_b = lanes_below(mb[c], pos_b);
+      b[c] = (v >= tb) && !(v >= ta);
+      const uint64_t mb = __builtin_amdgcn_ballot_w64(b[c]);
+      pos = lanes_below(mb, pos);
+      base += (uint32_t)__builtin_popcountll(mb);
     }
 #pragma unroll
     for (int c = 0; c < G; ++c) {
-      p[c] = p[c] || (b[c] && pos_b < (uint32_t)need_b);
-      pos_b += b[c] ? 1u : 0u;
-      base_b += (uint32_t)__builtin_popcountll(mb[c]);
+      if (b[c] && pos + 1u == (uint32_t)want) mine = (g * kWave + ln) * G + c;
+      pos += b[c] ? 1u : 0u;
     }
-    uint32_t pos = base;
-    uint64_t mk[G];
-#pragma unroll
-    for (int c = 0; c < G; ++c) {
-      mk[c] = __builtin_amdgcn_ballot_w64(p[c]);
-      pos = lanes_below(mk[c], pos);
-    }
-#pragma unroll
-    for (int c = 0; c < G; ++c) {
-      if (p[c] && pos < (uint32_t)limit) {
-        stage[pos] = make_uint2(__float_as_uint(x[g * G + c]), (uint32_t)((g * kWave + lane) * G + c));
-      }
-      pos += p[c] ? 1u : 0u;
-    }
-#pragma unroll
-    for (int c = 0; c < G; ++c) base += (uint32_t)__builtin_popcountll(mk[c]);
+    if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);
   }
+  // exactly one lane (or none) holds a column >= 0: a wavefront maximum returns it
+  int v = mine;
+  v = max(v, __builtin_amdgcn_update_dpp(-1, v, 0xB1, 0xf, 0xf, false));
+  v = max(v, __builtin_amdgcn_update_dpp(-1, v, 0x4E, 0xf, 0xf, false));
+  v = max(v, __builtin_amdgcn_update_dpp(-1, v, 0x141, 0xf, 0xf, false));
+  v = max(v, __builtin_amdgcn_update_dpp(-1, v, 0x140, 0xf, 0xf, false));
+  v = max(v, __builtin_amdgcn_update_dpp(-1, v, 0x142, 0xa, 0xf, false));
+  v = max(v, __builtin_amdgcn_update_dpp(-1, v, 0x143, 0xc, 0xf, false));
+  return __builtin_amdgcn_readlane(v, 63);
 }
 
 // Hand-scheduled search loops for four elements per lane (M <= 256 with 128-bit loads).  Same steps
@@ -392,30 +429,39 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
   float lo, hi;
   wave_max_and_negmin(mx, nm, hi, lo);
 
-  uint64_t m[E];
+  constexpr bool KEEP = E <= 16;              // masks of the last step stay in scalar registers
+  constexpr int ACC = KEEP ? 0 : (E * 3) / 8;  // wide rows: elements counted per lane (see count_ge_wide)
+  uint64_t m[KEEP ? E : 1];
+  auto count = [&](float t) -> int {
+    if constexpr (KEEP) {
+      return count_ge<E>(x, t, m);
+    } else {
+      return count_ge_wide<E, ACC>(x, t);
+    }
+  };
   if constexpr (EXACT) {
     // The loop ends on cnt == k, or once the fp32 midpoint stops changing: then no representable
     // threshold lies strictly inside (lo, hi).  The latter is tested every second step against the
-    // midpoint of two steps before (a converged search repeats its midpoint for ever, a live one
-    // never returns to an earlier midpoint); the extra steps leave lo and hi untouched.
+    // previous midpoint (a converged search repeats its midpoint for ever, a live one never returns to
+    // an earlier midpoint); the extra steps leave lo and hi untouched.
     bool hit = false;
+    float thres = lo;
     if constexpr (E == 4) {
       hit = search_exact4(x, lo, hi, k, m);
     } else {
-      float thres;
       float seen = lo;
       for (;;) {
         thres = (lo + hi) * 0.5f;
         if (!(thres < seen || thres > seen)) break;
         seen = thres;
-        int cnt = count_ge<E>(x, thres, m);
+        int cnt = count(thres);
         if (cnt == k) {
           hit = true;
           break;
         }
         move_bound(lo, hi, thres, cnt, k);
         thres = (lo + hi) * 0.5f;
-        cnt = count_ge<E>(x, thres, m);
+        cnt = count(thres);
         if (cnt == k) {
           hit = true;
           break;
@@ -424,12 +470,14 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
       }
     }
     if (hit) {
-      compact_masks<G, NG, false>(x, m, lane, k, stage_addr);
+      compact_masks<G, NG, false, !KEEP>(x, m, thres, thres, -1, lane, k, stage_addr);
     } else {
-      // Everything >= hi is in the answer (fewer than k of them unless hi is still the row maximum,
-      // in which case they are all equal); the rest comes from [lo, hi) by ascending column.
-      const int na = count_ge<E>(x, hi, m);
-      compact_two_level<G, NG>(x, lane, hi, lo, k, k - (na < k ? na : k), stage);
+      // Everything >= hi is taken first (cut at k by column when hi is still the row maximum and k
+      // or more tie there); the first k - na members of [lo, hi) follow: all columns up to the
+      // (k - na)-th member's column select against lo, the others against hi.
+      const int na = count(hi);
+      const int split = nth_column_in_band<G, NG>(x, lane, hi, lo, k - (na < k ? na : k));
+      compact_masks<G, NG, true, true>(x, nullptr, hi, lo, split, lane, k, stage_addr);
     }
   } else {
     int cnt = -1;
@@ -438,18 +486,18 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
     } else {
       for (int it = 0; it < max_iter; ++it) {
         const float thres = (lo + hi) * 0.5f;
-        cnt = count_ge<E>(x, thres, m);
-        // cnt == k: lo can from now on only move to thresholds that still count exactly k, so the
+        cnt = count(thres);
+        // cnt == k: from here on lo can only move to thresholds that still count exactly k, so the
         // selection is already final.
-        if (cnt == k) break;
         move_bound(lo, hi, thres, cnt, k);
+        if (cnt == k) break;
       }
     }
-    if (cnt < k) cnt = count_ge<E>(x, lo, m);  // the last step lowered hi (or none ran): m[] is not for lo
+    if (cnt < k) cnt = count(lo);  // the last step lowered hi (or none ran): the masks are not for lo
     if (cnt == k) {
-      compact_masks<G, NG, false>(x, m, lane, k, stage_addr);
+      compact_masks<G, NG, false, !KEEP>(x, m, lo, lo, -1, lane, k, stage_addr);
     } else {
-      compact_masks<G, NG, true>(x, m, lane, k, stage_addr);
+      compact_masks<G, NG, true, !KEEP>(x, m, lo, lo, -1, lane, k, stage_addr);
     }
   }
 }
@@ -546,6 +594,7 @@ const V v = load_streaming<G>(row + col0);
   float* ov = out_vals + r0 * (int64_t)k;
   IdxT* oi = out_idx + r0 * (int64_t)k;
   if (vec_store) {
+#pragma unroll 1
     for (int q = lane; q < (total >> 2); q += kWave) {
       const uint4 a = *reinterpret_cast<const uint4*>(stage + 4 * q);
       const uint4 b = *reinterpret_cast<const uint4*>(stage + 4 * q + 2);
@@ -557,6 +606,7 @@ const V v = load_streaming<G>(row + col0);
       }
     }
   } else {
+#pragma unroll 1
     for (int q = lane; q < total; q += kWave) {
       const uint2 a = stage[q];
       ov[q] = __uint_as_float(a.x);

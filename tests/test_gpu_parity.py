@@ -95,6 +95,23 @@ def test_tie_heavy_rows(M):
                 assert_parity(R, x, k, "early", mi, tag=f"{gen} M={M} k={k} mi={mi}")
 
 
+@pytest.mark.parametrize("M", [1280, 2048, 3000, 4096])
+def test_tie_heavy_wide_rows(M):
+    # wide rows count without keeping masks and select through the converged-search path under ties
+    R = _gpu()
+    for gen, seed in (("pool", 91), ("ints", 92), ("ties", 93)):
+        if gen == "pool":
+            x = workloads.from_pool(150, M, seed + M)
+        elif gen == "ints":
+            x = workloads.small_ints(150, M, seed + M, span=20)
+        else:
+            x = workloads.normal_ties(150, M, seed + M, p=0.5)
+        for k in (1, 64, 257, M // 2, M - 1):
+            assert_parity(R, x, k, "exact", tag=f"{gen} M={M} k={k}")
+            for mi in (0, 5, 30):
+                assert_parity(R, x, k, "early", mi, tag=f"{gen} M={M} k={k} mi={mi}")
+
+
 def test_all_equal_and_two_valued_rows():
     R = _gpu()
     x = np.full((40, 256), 3.25, dtype=np.float32)
