@@ -32,6 +32,8 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
+    # regenerate the inline-assembly search loops (a no-op when the committed file is current)
+    subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_search_loops.py")], stdout=subprocess.DEVNULL)
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH])

@@ -279,116 +279,9 @@ __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int 
   return __builtin_amdgcn_readlane(v, 63);
 }
 
-// Hand-scheduled search loops for four elements per lane (M <= 256 with 128-bit loads).  Same steps
-// as the generic loops below, written out so that a step costs about 7 vector and 11 scalar
-// instructions: the wave-uniform bounds are moved with one v_mov under a scalar branch.  Masks of the
-// last evaluated threshold come back in m[0..3].
-#define RTOPK_MID "v_add_f32 %[t], %[lo], %[hi]\n\tv_mul_f32 %[t], 0.5, %[t]\n\t"
-#define RTOPK_COUNT4                                                     \
-  "v_cmp_ge_f32 %[m0], %[x0], %[t]\n\t"                                   \
-  "v_cmp_ge_f32 %[m1], %[x1], %[t]\n\t"                                   \
-  "v_cmp_ge_f32 %[m2], %[x2], %[t]\n\t"                                   \
-  "v_cmp_ge_f32 %[m3], %[x3], %[t]\n\t"                                   \
-  "s_bcnt1_i32_b64 %[c0], %[m0]\n\t"                                      \
-  "s_bcnt1_i32_b64 %[c1], %[m1]\n\t"                                      \
-  "s_bcnt1_i32_b64 %[c2], %[m2]\n\t"                                      \
-  "s_bcnt1_i32_b64 %[c3], %[m3]\n\t"                                      \
-  "s_add_i32 %[c0], %[c0], %[c1]\n\t"                                     \
-  "s_add_i32 %[c2], %[c2], %[c3]\n\t"                                     \
-  "s_add_i32 %[c0], %[c0], %[c2]\n\t"
-
-// Algorithm 1 at epsilon = 0.  Returns true when a step counted exactly k (m[] then selects the
-// answer); false when the search converged first (lo, hi hold the final bounds).  Steps alternate
-// between two code copies A and B that keep their midpoints in different registers, so that copy A
-// can compare its midpoint with the previous one: equal (or unordered) means converged.
-__device__ __forceinline__ bool search_exact4(const float (&x)[4], float& lo, float& hi, int k, uint64_t (&m)[4]) {
-  float t, u;
-  int c0, c1, c2, c3, hit;
-  asm volatile(
-      // ---- copy B (entry): midpoint in u, no convergence test
-      ".Lrtopk_b_%=:\n\t"
-      "v_add_f32 %[u], %[lo], %[hi]\n\t"
-      "v_mul_f32 %[u], 0.5, %[u]\n\t"
-      "v_cmp_ge_f32 %[m0], %[x0], %[u]\n\t"
-      "v_cmp_ge_f32 %[m1], %[x1], %[u]\n\t"
-      "v_cmp_ge_f32 %[m2], %[x2], %[u]\n\t"
-      "v_cmp_ge_f32 %[m3], %[x3], %[u]\n\t"
-      "s_bcnt1_i32_b64 %[c0], %[m0]\n\t"
-      "s_bcnt1_i32_b64 %[c1], %[m1]\n\t"
-      "s_bcnt1_i32_b64 %[c2], %[m2]\n\t"
-      "s_bcnt1_i32_b64 %[c3], %[m3]\n\t"
-      "s_add_i32 %[c0], %[c0], %[c1]\n\t"
-      "s_add_i32 %[c2], %[c2], %[c3]\n\t"
-      "s_add_i32 %[c0], %[c0], %[c2]\n\t"
-      "s_cmp_lt_i32 %[c0], %[k]\n\t"
-      "s_cbranch_scc1 .Lrtopk_bless_%=\n\t"
-      "s_cmp_gt_i32 %[c0], %[k]\n\t"
-      "v_mov_b32 %[lo], %[u]\n\t"
-      "s_cbranch_scc1 .Lrtopk_a_%=\n\t"
-      "s_branch .Lrtopk_hit_%=\n\t"
-      ".Lrtopk_bless_%=:\n\t"
-      "v_mov_b32 %[hi], %[u]\n\t"
-      // ---- copy A: midpoint in t, compared with copy B's
-      ".Lrtopk_a_%=:\n\t"
-      RTOPK_MID
-      "v_cmp_lg_f32 vcc, %[t], %[u]\n\t"
-      "s_cbranch_vccz .Lrtopk_conv_%=\n\t"
-      RTOPK_COUNT4
-      "s_cmp_lt_i32 %[c0], %[k]\n\t"
-      "s_cbranch_scc1 .Lrtopk_aless_%=\n\t"
-      "s_cmp_gt_i32 %[c0], %[k]\n\t"
-      "v_mov_b32 %[lo], %[t]\n\t"
-      "s_cbranch_scc1 .Lrtopk_b_%=\n\t"
-      "s_branch .Lrtopk_hit_%=\n\t"
-      ".Lrtopk_aless_%=:\n\t"
-      "v_mov_b32 %[hi], %[t]\n\t"
-      "s_branch .Lrtopk_b_%=\n\t"
-      ".Lrtopk_conv_%=:\n\t"
-      "s_mov_b32 %[hit], 0\n\t"
-      "s_branch .Lrtopk_end_%=\n\t"
-      ".Lrtopk_hit_%=:\n\t"
-      "s_mov_b32 %[hit], 1\n\t"
-      ".Lrtopk_end_%=:"
-      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [u] "=&v"(u), [m0] "=&s"(m[0]), [m1] "=&s"(m[1]),
-        [m2] "=&s"(m[2]), [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3),
-        [hit] "=&s"(hit)
-      : [x0] "v"(x[0]), [x1] "v"(x[1]), [x2] "v"(x[2]), [x3] "v"(x[3]), [k] "s"(k)
-      : "vcc", "scc");
-  return hit != 0;
-}
-
-// Algorithm 2: max_iter steps (fewer when a step counts exactly k).  Returns the count of the last
-// step, or -1 when no step ran; when it is >= k, m[] holds the masks of x >= lo.
-__device__ __forceinline__ int search_early4(const float (&x)[4], float& lo, float& hi, int k, int max_iter,
-                                             uint64_t (&m)[4]) {
-  float t;
-  int c0, c1, c2, c3, it;
-  asm volatile(
-      "s_mov_b32 %[c0], -1\n\t"
-      "s_sub_u32 %[it], %[n], 1\n\t"
-      "s_cbranch_scc1 .Lrtopk_end_%=\n\t"
-      ".Lrtopk_top_%=:\n\t"
-      RTOPK_MID
-      RTOPK_COUNT4
-      "s_cmp_lt_i32 %[c0], %[k]\n\t"
-      "s_cbranch_scc1 .Lrtopk_less_%=\n\t"
-      "s_cmp_gt_i32 %[c0], %[k]\n\t"
-      "v_mov_b32 %[lo], %[t]\n\t"
-      "s_cbranch_scc0 .Lrtopk_end_%=\n\t"
-      "s_sub_u32 %[it], %[it], 1\n\t"
-      "s_cbranch_scc0 .Lrtopk_top_%=\n\t"
-      "s_branch .Lrtopk_end_%=\n\t"
-      ".Lrtopk_less_%=:\n\t"
-      "v_mov_b32 %[hi], %[t]\n\t"
-      "s_sub_u32 %[it], %[it], 1\n\t"
-      "s_cbranch_scc0 .Lrtopk_top_%=\n\t"
-      ".Lrtopk_end_%=:"
-      : [lo] "+v"(lo), [hi] "+v"(hi), [t] "=&v"(t), [m0] "=&s"(m[0]), [m1] "=&s"(m[1]), [m2] "=&s"(m[2]),
-        [m3] "=&s"(m[3]), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3), [it] "=&s"(it)
-      : [x0] "v"(x[0]), [x1] "v"(x[1]), [x2] "v"(x[2]), [x3] "v"(x[3]), [k] "s"(k), [n] "s"(max_iter)
-      : "vcc", "scc");
-  return c0;
-}
+// Hand-scheduled search loops for 2, 4 and 8 values per lane: search_exact_asm / search_early_asm
+// (generated by gen_search_loops.py; same steps as the generic loops in select_row).
+#include "rtopk_search_loops.inc"
 
 // Search and selection for one row held as x[E] (columns past M hold -inf and are never chosen).
 //   EXACT: Algorithm 1 at epsilon = 0; otherwise Algorithm 2 with max_iter steps.
@@ -429,8 +322,11 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
   float lo, hi;
   wave_max_and_negmin(mx, nm, hi, lo);
 
-  constexpr bool KEEP = E <= 16;              // masks of the last step stay in scalar registers
-  constexpr int ACC = KEEP ? 0 : (E * 3) / 8;  // wide rows: elements counted per lane (see count_ge_wide)
+  constexpr bool ASM = (E == 2 || E == 4 || E == 8);  // hand-scheduled loops exist for these widths
+  constexpr bool KEEP = E <= 8;                       // masks of the last step stay in scalar registers
+  // wider rows: ACC of the E elements are counted per lane, which balances vector against scalar work
+  // (2*ACC + (E-ACC) + ~11 vector against 2*(E-ACC) + ~8 scalar instructions per step)
+  constexpr int ACC = KEEP ? 0 : (E - 3) / 3;
   uint64_t m[KEEP ? E : 1];
   auto count = [&](float t) -> int {
     if constexpr (KEEP) {
@@ -446,8 +342,8 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
     // an earlier midpoint); the extra steps leave lo and hi untouched.
     bool hit = false;
     float thres = lo;
-    if constexpr (E == 4) {
-      hit = search_exact4(x, lo, hi, k, m);
+    if constexpr (ASM) {
+      hit = search_exact_asm(x, lo, hi, k, m);
     } else {
       float seen = lo;
       for (;;) {
@@ -481,8 +377,8 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
     }
   } else {
     int cnt = -1;
-    if constexpr (E == 4) {
-      cnt = search_early4(x, lo, hi, k, max_iter, m);
+    if constexpr (ASM) {
+      cnt = search_early_asm(x, lo, hi, k, max_iter, m);
     } else {
       for (int it = 0; it < max_iter; ++it) {
         const float thres = (lo + hi) * 0.5f;
