@@ -74,6 +74,21 @@ int rtopk_rowwise_u8(const float* in, int64_t N, int32_t M, int32_t k, int32_t m
 int rtopk_rowwise_exact_u8(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, uint8_t* out_idx,
                            void* stream);
 
+/*
+ * Precision-bounded selection: Algorithm 1 with epsilon = eps_rel * |max(row)| (Section 3.1: epsilon
+ * bounds the width of the "borderline" and with it the number of steps; Appendix B, Fig. 7 sweeps it).
+ * The search ends when a step counts exactly k, when hi - lo <= epsilon, or when no fp32 value lies
+ * strictly between lo and hi.  Everything >= hi is then taken, and the lowest columns of [lo, hi) fill
+ * up to k, so every selected value is >= (k-th largest) - epsilon and every rejected one is
+ * < (k-th largest) + epsilon.  eps_rel == 0 gives exactly rtopk_rowwise_exact's output.
+ *   eps_rel   : >= 0 (negative or NaN: RTOPK_ERR_BAD_EPSILON).
+ *   out_iters : optional (may be NULL) device int32_t[N]; receives the exit iteration of each row's
+ *               loop as Tables 1 and 5 count it: the number of midpoints evaluated when one of them
+ *               counted exactly k, one more than that when the loop ended through its guard.
+ */
+int rtopk_rowwise_eps(const float* in, int64_t N, int32_t M, int32_t k, float eps_rel, float* out_vals,
+                      int32_t* out_idx, int32_t* out_iters, void* stream);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* rtopk_status_string(int status);
 

@@ -11,6 +11,7 @@ from .rtopk import (  # noqa: F401
     load_library,
     rtopk_max_m,
     rtopk_rowwise,
+    rtopk_rowwise_eps,
     rtopk_rowwise_exact,
     rtopk_rowwise_exact_u8,
     rtopk_rowwise_u8,

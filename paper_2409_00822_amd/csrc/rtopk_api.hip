@@ -10,26 +10,29 @@
 namespace {
 
 constexpr int kMaxM = 4096;
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 200;  // 0.2.0
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-// Shared body of the four selection entry points.
-//   exact: Algorithm 1 at epsilon = 0; otherwise Algorithm 2 with max_iter steps.
-//   u8:    out_idx is uint8_t[N][k] (requires M <= 256), else int32_t[N][k].
-int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, bool exact, float* out_vals,
-        void* out_idx, bool u8, void* stream) {
+// Shared body of the selection entry points.
+//   mode: rtopk::kEarly (Algorithm 2, max_iter steps), kExact (Algorithm 1, epsilon = 0) or
+//         kEps (Algorithm 1, epsilon = eps_rel * |max|, optional exit-iteration output).
+//   u8:   out_idx is uint8_t[N][k] (requires M <= 256), else int32_t[N][k].
+int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float eps_rel, int mode, float* out_vals,
+        void* out_idx, int32_t* out_iters, bool u8, void* stream) {
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
-  if (!exact && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
+  if (mode == rtopk::kEarly && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
+  if (mode == rtopk::kEps && !(eps_rel >= 0.0f)) return RTOPK_ERR_BAD_EPSILON;
   if (M > kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
   if (N == 0) return RTOPK_OK;
   if (!in || !out_vals || !out_idx) return RTOPK_ERR_NULL_POINTER;
-  if (!aligned(in, 4) || !aligned(out_vals, 4) || (!u8 && !aligned(out_idx, 4))) return RTOPK_ERR_MISALIGNED;
+  if (!aligned(in, 4) || !aligned(out_vals, 4) || (!u8 && !aligned(out_idx, 4)) || !aligned(out_iters, 4))
+    return RTOPK_ERR_MISALIGNED;
 
   // k == M: every column is selected.  Algorithm 2 with zero steps returns the first k columns,
   // which is that answer without a search that would otherwise run down to float resolution.
-  if (exact && k == M) {
-    exact = false;
+  if (mode == rtopk::kExact && k == M) {
+    mode = rtopk::kEarly;
     max_iter = 0;
   }
 
@@ -39,6 +42,8 @@ int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, bool
   a.M = M;
   a.k = k;
   a.max_iter = max_iter;
+  a.eps_rel = eps_rel;
+  a.out_iters = out_iters;
   a.out_vals = out_vals;
   a.out_idx = out_idx;
   a.vec_store = (k % 4 == 0) && aligned(out_vals, 16) && aligned(out_idx, u8 ? 4 : 16);
@@ -56,13 +61,15 @@ int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, bool
       }
     }
     const bool full = (M == 256 * ng);
-    err = exact ? rtopk::launch_g4_exact(ng, full, u8, a) : rtopk::launch_g4_early(ng, full, u8, a);
+    err = mode == rtopk::kExact   ? rtopk::launch_g4_exact(ng, full, u8, a)
+          : mode == rtopk::kEarly ? rtopk::launch_g4_early(ng, full, u8, a)
+                                  : rtopk::launch_g4_eps(ng, full, a);
   } else if (M > 64 && M <= 128 && M % 2 == 0 && aligned(in, 8)) {
-    err = rtopk::launch_small(2, 1, M == 128, exact, u8, a);
+    err = rtopk::launch_small(2, 1, M == 128, mode, u8, a);
   } else {
     int ng = 1;
     while (64 * ng < M) ng <<= 1;
-    err = rtopk::launch_small(1, ng, M == 64 * ng, exact, u8, a);
+    err = rtopk::launch_small(1, ng, M == 64 * ng, mode, u8, a);
   }
   return err == hipSuccess ? RTOPK_OK : RTOPK_ERR_LAUNCH;
 }
@@ -73,22 +80,27 @@ extern "C" {
 
 int rtopk_rowwise(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
                   int32_t* out_idx, void* stream) {
-  return run(in, N, M, k, max_iter, false, out_vals, out_idx, false, stream);
+  return run(in, N, M, k, max_iter, 0.0f, rtopk::kEarly, out_vals, out_idx, nullptr, false, stream);
 }
 
 int rtopk_rowwise_exact(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx,
                         void* stream) {
-  return run(in, N, M, k, 0, true, out_vals, out_idx, false, stream);
+  return run(in, N, M, k, 0, 0.0f, rtopk::kExact, out_vals, out_idx, nullptr, false, stream);
 }
 
 int rtopk_rowwise_u8(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
                      uint8_t* out_idx, void* stream) {
-  return run(in, N, M, k, max_iter, false, out_vals, out_idx, true, stream);
+  return run(in, N, M, k, max_iter, 0.0f, rtopk::kEarly, out_vals, out_idx, nullptr, true, stream);
 }
 
 int rtopk_rowwise_exact_u8(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, uint8_t* out_idx,
                            void* stream) {
-  return run(in, N, M, k, 0, true, out_vals, out_idx, true, stream);
+  return run(in, N, M, k, 0, 0.0f, rtopk::kExact, out_vals, out_idx, nullptr, true, stream);
+}
+
+int rtopk_rowwise_eps(const float* in, int64_t N, int32_t M, int32_t k, float eps_rel, float* out_vals,
+                      int32_t* out_idx, int32_t* out_iters, void* stream) {
+  return run(in, N, M, k, 0, eps_rel, rtopk::kEps, out_vals, out_idx, out_iters, false, stream);
 }
 
 const char* rtopk_status_string(int status) {

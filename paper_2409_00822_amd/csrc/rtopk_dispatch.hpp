@@ -7,10 +7,19 @@
 
 namespace rtopk {
 
+// Which algorithm of the paper (Section 3.1) a kernel instance runs.
+enum Mode : int {
+  kEarly = 0,  // Algorithm 2: max_iter steps, one-pass selection against min
+  kExact = 1,  // Algorithm 1 at epsilon = 0
+  kEps = 2     // Algorithm 1 with epsilon = eps_rel * |max|, optional exit-iteration output
+};
+
 struct LaunchArgs {
   const float* in;
   int64_t N;
   int M, k, max_iter;
+  float eps_rel;       // kEps only
+  int32_t* out_iters;  // kEps only, may be null
   float* out_vals;
   void* out_idx;
   int vec_store;  // 1: k % 4 == 0 and both outputs aligned for 128-bit (values) / whole-word (columns) stores
@@ -21,7 +30,8 @@ struct LaunchArgs {
 // full = (M == 64*G*ng): no column-validity tests in the kernel.
 hipError_t launch_g4_exact(int ng, bool full, bool u8, const LaunchArgs& a);
 hipError_t launch_g4_early(int ng, bool full, bool u8, const LaunchArgs& a);
+hipError_t launch_g4_eps(int ng, bool full, const LaunchArgs& a);  // int32 columns only
 // Narrow rows and scalar-load fallback (any M, 4-byte alignment).
-hipError_t launch_small(int g, int ng, bool full, bool exact, bool u8, const LaunchArgs& a);
+hipError_t launch_small(int g, int ng, bool full, int mode, bool u8, const LaunchArgs& a);
 
 }  // namespace rtopk

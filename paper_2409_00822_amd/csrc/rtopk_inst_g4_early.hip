@@ -7,9 +7,9 @@ template <int NG>
 static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
   constexpr int R = rows_per_wave(4 * NG);
   if constexpr (NG == 1) {
-    if (u8) return full ? launch<4, NG, R, true, false, uint8_t>(a) : launch<4, NG, R, false, false, uint8_t>(a);
+    if (u8) return full ? launch<4, NG, R, true, kEarly, uint8_t>(a) : launch<4, NG, R, false, kEarly, uint8_t>(a);
   }
-  return full ? launch<4, NG, R, true, false, int32_t>(a) : launch<4, NG, R, false, false, int32_t>(a);
+  return full ? launch<4, NG, R, true, kEarly, int32_t>(a) : launch<4, NG, R, false, kEarly, int32_t>(a);
 }
 
 hipError_t launch_g4_early(int ng, bool full, bool u8, const LaunchArgs& a) {

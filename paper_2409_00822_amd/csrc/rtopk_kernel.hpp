@@ -284,10 +284,13 @@ __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int 
 #include "rtopk_search_loops.inc"
 
 // Search and selection for one row held as x[E] (columns past M hold -inf and are never chosen).
-//   EXACT: Algorithm 1 at epsilon = 0; otherwise Algorithm 2 with max_iter steps.
-template <int G, int NG, bool FULL, bool EXACT>
-__device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, int M, int k, int max_iter,
-                                           uint2* stage) {
+//   MODE: kExact = Algorithm 1 at epsilon = 0, kEarly = Algorithm 2 with max_iter steps,
+//         kEps = Algorithm 1 with epsilon = eps_rel * |max|.
+// Returns the exit iteration of the search loop (kEps only; 0 otherwise): the number of midpoints
+// evaluated when one of them counted exactly k, one more when the loop ended through its guard.
+template <int G, int NG, bool FULL, int MODE>
+__device__ __forceinline__ int select_row(const float (&x)[G * NG], int lane, int M, int k, int max_iter,
+                                          float eps_rel, uint2* stage) {
   constexpr int E = G * NG;
   const uint32_t stage_addr = (uint32_t)(uintptr_t)stage;  // LDS byte address
 
@@ -335,7 +338,7 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
       return count_ge_wide<E, ACC>(x, t);
     }
   };
-  if constexpr (EXACT) {
+  if constexpr (MODE == kExact) {
     // The loop ends on cnt == k, or once the fp32 midpoint stops changing: then no representable
     // threshold lies strictly inside (lo, hi).  The latter is tested every second step against the
     // previous midpoint (a converged search repeats its midpoint for ever, a live one never returns to
@@ -375,6 +378,35 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
       const int split = nth_column_in_band<G, NG>(x, lane, hi, lo, k - (na < k ? na : k));
       compact_masks<G, NG, true, true>(x, nullptr, hi, lo, split, lane, k, stage_addr);
     }
+    return 0;
+  } else if constexpr (MODE == kEps) {
+    // Algorithm 1 as printed, with epsilon = eps_rel * |max| and the same two readings as the exact
+    // mode: the loop also ends when the midpoint is not strictly inside (lo, hi), and the selection
+    // after a guard exit takes everything >= hi, then the first columns of [lo, hi).
+    const float eps = eps_rel * __builtin_fabsf(hi);
+    bool hit = false;
+    float thres = lo;
+    int steps = 0;
+    while (hi - lo > eps) {
+      const float mid = (lo + hi) * 0.5f;
+      if (!(mid > lo && mid < hi)) break;
+      thres = mid;
+      ++steps;
+      const int cnt = count(thres);
+      if (cnt == k) {
+        hit = true;
+        break;
+      }
+      move_bound(lo, hi, thres, cnt, k);
+    }
+    if (hit) {
+      compact_masks<G, NG, false, !KEEP>(x, m, thres, thres, -1, lane, k, stage_addr);
+      return steps;
+    }
+    const int na = count(hi);
+    const int split = nth_column_in_band<G, NG>(x, lane, hi, lo, k - (na < k ? na : k));
+    compact_masks<G, NG, true, true>(x, nullptr, hi, lo, split, lane, k, stage_addr);
+    return steps + 1;
   } else {
     int cnt = -1;
     if constexpr (ASM) {
@@ -395,6 +427,7 @@ __device__ __forceinline__ void select_row(const float (&x)[G * NG], int lane, i
     } else {
       compact_masks<G, NG, true, !KEEP>(x, m, lo, lo, -1, lane, k, stage_addr);
     }
+    return 0;
   }
 }
 
@@ -432,10 +465,11 @@ __device__ __forceinline__ typename VecOf<G>::type load_streaming(const float* p
   }
 }
 
-template <int G, int NG, int R, bool FULL, bool EXACT, typename IdxT>
+template <int G, int NG, int R, bool FULL, int MODE, typename IdxT>
 __global__ void __launch_bounds__(256)
-    rtopk_wave_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter,
-                      float* __restrict__ out_vals, IdxT* __restrict__ out_idx, int vec_store) {
+    rtopk_wave_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
+                      float* __restrict__ out_vals, IdxT* __restrict__ out_idx, int32_t* __restrict__ out_iters,
+                      int vec_store) {
   constexpr int E = G * NG;
   extern __shared__ uint2 stage_all[];  // [waves per block][R * k] (value bits, column)
 
@@ -479,7 +513,12 @@ const V v = load_streaming<G>(row + col0);
   // Searching and selecting stages, row by row.
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
-    if (rr < nrows) select_row<G, NG, FULL, EXACT>(x[rr], lane, M, k, max_iter, stage + (size_t)rr * k);
+    if (rr < nrows) {
+      const int it = select_row<G, NG, FULL, MODE>(x[rr], lane, M, k, max_iter, eps_rel, stage + (size_t)rr * k);
+      if constexpr (MODE == kEps) {
+        if (out_iters != nullptr && lane == 0) out_iters[r0 + rr] = it;
+      }
+    }
   }
 
   // Dump: the wavefront's nrows*k staged pairs are contiguous in both output arrays.
@@ -513,7 +552,7 @@ const V v = load_streaming<G>(row + col0);
 
 // ---- host-side launcher -------------------------------------------------------------------------------
 
-template <int G, int NG, int R, bool FULL, bool EXACT, typename IdxT>
+template <int G, int NG, int R, bool FULL, int MODE, typename IdxT>
 hipError_t launch(const LaunchArgs& a) {
   // LDS per wavefront: R*k staged pairs of 8 bytes; at most 64 KiB per block.
   const size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
@@ -522,9 +561,9 @@ hipError_t launch(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((rtopk_wave_kernel<G, NG, R, FULL, EXACT, IdxT>), dim3((unsigned)blocks), dim3(waves * kWave),
-                     per_wave * waves, a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.out_vals,
-                     static_cast<IdxT*>(a.out_idx), a.vec_store);
+  hipLaunchKernelGGL((rtopk_wave_kernel<G, NG, R, FULL, MODE, IdxT>), dim3((unsigned)blocks), dim3(waves * kWave),
+                     per_wave * waves, a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
+                     static_cast<IdxT*>(a.out_idx), a.out_iters, a.vec_store);
   return hipGetLastError();
 }
 

@@ -33,7 +33,9 @@ def load_library() -> ctypes.CDLL:
         lib.rtopk_rowwise_u8.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_exact.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_exact_u8.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        lib.rtopk_rowwise_eps.argtypes = [vp, i64, i32, i32, ctypes.c_float, vp, vp, vp, vp]
         for fn in (lib.rtopk_rowwise, lib.rtopk_rowwise_u8, lib.rtopk_rowwise_exact, lib.rtopk_rowwise_exact_u8,
+                   lib.rtopk_rowwise_eps,
                    lib.rtopk_version, lib.rtopk_max_m):
             fn.restype = ctypes.c_int
         lib.rtopk_status_string.argtypes = [ctypes.c_int]
@@ -113,3 +115,20 @@ def rtopk_rowwise_exact_u8(x, k: int, out_vals=None, out_idx=None):
     _check(load_library().rtopk_rowwise_exact_u8(x.data_ptr(), N, M, k, out_vals.data_ptr(), out_idx.data_ptr(),
                                                  stream))
     return out_vals, out_idx
+
+
+def rtopk_rowwise_eps(x, k: int, eps_rel: float, out_vals=None, out_idx=None, out_iters=None, want_iters: bool = False):
+    """Algorithm 1 with precision epsilon = eps_rel * |max(row)|.  Returns (values, columns) or, when
+    `want_iters` is set or `out_iters` is given, (values, columns, exit iterations [N] i32)."""
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.int32)
+    if out_iters is None and want_iters:
+        out_iters = torch.empty((N,), dtype=torch.int32, device=x.device)
+    if out_iters is not None and not (out_iters.is_cuda and out_iters.dtype == torch.int32
+                                      and out_iters.is_contiguous() and tuple(out_iters.shape) == (N,)):
+        raise ValueError("out_iters must be a contiguous [N] int32 GPU tensor")
+    _check(load_library().rtopk_rowwise_eps(x.data_ptr(), N, M, k, float(eps_rel), out_vals.data_ptr(),
+                                            out_idx.data_ptr(), out_iters.data_ptr() if out_iters is not None else None,
+                                            stream))
+    return (out_vals, out_idx, out_iters) if out_iters is not None else (out_vals, out_idx)

@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert {"rtopk_rowwise", "rtopk_rowwise_exact", "rtopk_rowwise_u8", "rtopk_rowwise_exact_u8",
+    assert {"rtopk_rowwise", "rtopk_rowwise_exact", "rtopk_rowwise_u8", "rtopk_rowwise_exact_u8", "rtopk_rowwise_eps",
             "rtopk_status_string", "rtopk_version", "rtopk_max_m"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -64,6 +64,14 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fe(p, 4, 4100, 32, p, p, None) == -4
     assert lib.rtopk_rowwise_u8(p, 4, 260, 32, 8, p, p, None) == -4
     assert lib.rtopk_rowwise_exact_u8(p, 4, 260, 32, p, p, None) == -4
+    fz = lib.rtopk_rowwise_eps
+    fz.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
+                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert fz(p, 4, 256, 32, -1e-3, p, p, None, None) == -7
+    assert fz(p, 4, 256, 32, float("nan"), p, p, None, None) == -7
+    assert fz(p, 0, 256, 32, 0.5, None, None, None, None) == 0
+    assert fz(p, 4, 256, 32, 0.5, p, p, p + 2, None) == -5
+    assert fz(p, 4, 4100, 32, 0.5, p, p, None, None) == -4
     assert f(p + 2, 4, 256, 32, 8, p, p, None) == -5
     assert f(p, 4, 256, 32, 8, p + 1, p, None) == -5
     assert f(p, 4, 256, 32, 8, p, p + 2, None) == -5

@@ -178,6 +178,77 @@ def test_writes_stay_inside_the_outputs_and_nonfinite_inputs_terminate():
     assert np.array_equal(oi.cpu().numpy()[clean], ei)
 
 
+# ----------------------------------------------------------------------------------------------
+# Algorithm 1 with a precision epsilon, and its exit-iteration output
+# ----------------------------------------------------------------------------------------------
+def assert_eps_parity(R, x_np, k, eps_rel, tag=""):
+    xd = torch.from_numpy(x_np).cuda()
+    gv, gi, gt = R.rtopk_rowwise_eps(xd, k, eps_rel, want_iters=True)
+    torch.cuda.synchronize()
+    ov, oi, ot = oracle.alg1(x_np, k, eps_rel=eps_rel, collect=1)
+    gi, gt = gi.cpu().numpy(), gt.cpu().numpy()
+    if not np.array_equal(gi, oi):
+        bad = np.nonzero((gi != oi).any(axis=1))[0]
+        raise AssertionError(f"{tag} index mismatch in {bad.size} rows; first {bad[0]}: gpu {gi[bad[0]]} oracle {oi[bad[0]]}")
+    assert np.array_equal(bits(gv.cpu().numpy()), bits(ov)), f"{tag} value bits differ"
+    assert np.array_equal(gt, ot), f"{tag} exit iterations differ"
+
+
+@pytest.mark.parametrize("N,M,ks", [(9, 7, (1, 3, 7)), (257, 128, (16, 128)), (4099, 256, (1, 32, 128, 256)),
+                                     (130, 300, (32,)), (515, 512, (64,)), (129, 768, (96,)), (259, 1024, (128,)),
+                                     (35, 3000, (64,)), (70, 4096, (256,)), (9, 4095, (7,)), (100, 100, (12,))])
+def test_eps_mode_small_shapes(N, M, ks):
+    R = _gpu()
+    x = workloads.normal(N, M, seed=N * 31 + M)
+    for k in ks:
+        for eps in (0.0, 1e-6, 1e-4, 1e-2, 0.3, 5.0):
+            assert_eps_parity(R, x, k, eps, tag=f"N={N} M={M} k={k} eps={eps}")
+
+
+@pytest.mark.parametrize("M", [8, 64, 256, 1024, 2048])
+def test_eps_mode_tie_heavy_and_negative_rows(M):
+    R = _gpu()
+    xs = [workloads.from_pool(300, M, 55 + M), workloads.small_ints(300, M, 56 + M, span=4),
+          -np.abs(workloads.normal(300, M, 57 + M)) - 1.0]  # all-negative rows: epsilon uses |max|
+    for x in xs:
+        for k in sorted({1, max(1, M // 8), M // 2, M}):
+            for eps in (0.0, 1e-4, 0.05):
+                assert_eps_parity(R, x, k, eps, tag=f"M={M} k={k} eps={eps}")
+
+
+def test_eps_zero_equals_exact_entry_point_and_iters_are_optional():
+    R = _gpu()
+    x = workloads.normal_ties(6000, 256, seed=58, p=0.2)
+    xd = torch.from_numpy(x).cuda()
+    ev, ei = R.rtopk_rowwise_exact(xd, 32)
+    gv, gi = R.rtopk_rowwise_eps(xd, 32, 0.0)  # no iteration output requested
+    torch.cuda.synchronize()
+    assert torch.equal(ei, gi) and torch.equal(ev.view(torch.int32), gv.view(torch.int32))
+
+
+def test_exit_iteration_statistics_of_table1_on_the_gpu():
+    # Table 1 (Section 3.1) reproduced by the kernel's own iteration output: eps' = 1e-4, M = 256, N(0,1).
+    from conftest import read_table
+
+    R = _gpu()
+    header, rows = read_table("table1_exit_cumulative.txt")
+    x = workloads.normal(100000, 256, seed=1001)
+    xd = torch.from_numpy(x).cuda()
+    for col, k in enumerate(int(h[1:]) for h in header[1:]):
+        _, _, it = R.rtopk_rowwise_eps(xd, k, 1e-4, want_iters=True)
+        it = it.cpu().numpy()
+        for row in rows:
+            t, paper = int(row[0]), float(row[1 + col])
+            assert abs(float((it <= t).mean() * 100.0) - paper) < 1.0, (k, t)
+
+
+def test_config1_eps_mode_full_size():
+    R = _gpu()
+    x = workloads.make("c1_maxk")
+    assert_eps_parity(R, x, 32, 1e-4, tag="c1 eps=1e-4")
+    assert_eps_parity(R, x, 32, 0.0, tag="c1 eps=0")
+
+
 def test_empty_batch_and_error_codes_on_device():
     R = _gpu()
     x = torch.empty((0, 256), dtype=torch.float32, device="cuda")
@@ -186,6 +257,10 @@ def test_empty_batch_and_error_codes_on_device():
     y = torch.zeros((4, 8), dtype=torch.float32, device="cuda")
     with pytest.raises(R.RTopKError):
         R.rtopk_rowwise(y, 3, -1)
+    with pytest.raises(R.RTopKError):
+        R.rtopk_rowwise_eps(y, 3, -0.5)
+    with pytest.raises(R.RTopKError):
+        R.rtopk_rowwise_eps(y, 3, float("nan"))
 
 
 def test_other_stream():

@@ -142,6 +142,34 @@ def test_midpoint_guard_fires_only_when_no_float_lies_strictly_between():
             assert inside.all()
 
 
+@pytest.mark.parametrize("eps_rel", [1e-1, 1e-2, 1e-4])
+def test_alg1_with_epsilon_stays_within_the_stated_error_band(eps_rel):
+    # Section 3.1: epsilon is the maximum width of the borderline.  So every selected value must be
+    # >= (k-th largest) - epsilon and every rejected value < (k-th largest) + epsilon, with
+    # epsilon = eps_rel * |max|; checked against a full sort, not against the oracle's own bounds.
+    for gen in ("normal", "ties"):
+        x = workloads.normal(4000, 256, seed=71) if gen == "normal" else workloads.normal_ties(4000, 256, seed=72, p=0.3)
+        for k in (1, 32, 128, 255):
+            vals, idx, iters = oracle.alg1(x, k, eps_rel=eps_rel, collect=1)
+            check_invariants(x, vals, idx, k, exact=False)
+            srt = np.sort(x, axis=1)[:, ::-1]
+            kth = srt[:, k - 1].astype(np.float64)
+            eps = np.float64(np.float32(eps_rel)) * np.abs(srt[:, 0].astype(np.float64))
+            mask = np.zeros(x.shape, dtype=bool)
+            np.put_along_axis(mask, idx.astype(np.int64), True, axis=1)
+            sel_min = np.where(mask, x, np.inf).min(axis=1)
+            unsel_max = np.where(mask, -np.inf, x).max(axis=1)
+            slack = 1e-6 * np.abs(srt[:, 0])  # fp32 rounding of hi - lo and of eps itself
+            assert (sel_min >= kth - eps - slack).all()
+            assert (unsel_max <= kth + eps + slack).all()
+            assert iters.max() <= 1 + math.ceil(math.log2(1.0 / eps_rel)) + 2  # D / 2^t <= eps_rel * |max|, D <= 2|max|
+    # a larger epsilon can only end the loop earlier
+    x = workloads.normal(2000, 256, seed=73)
+    it_small = oracle.alg1(x, 32, eps_rel=1e-4, want_select=False)[2]
+    it_big = oracle.alg1(x, 32, eps_rel=1e-1, want_select=False)[2]
+    assert (it_big <= it_small).all() and (it_big < it_small).any()
+
+
 # --------------------------------------------------------------------------------------------
 # exit-iteration statistics of Algorithm 1 (Tables 1 and 5, Eq. 4)
 # --------------------------------------------------------------------------------------------
