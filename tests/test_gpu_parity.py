@@ -263,6 +263,37 @@ def test_empty_batch_and_error_codes_on_device():
         R.rtopk_rowwise_eps(y, 3, float("nan"))
 
 
+def test_hip_graph_capture_and_replay():
+    # One launch per call, no allocation, no memset: the entry points can be recorded into a HIP graph.
+    # Replays are interleaved with eager work and checked every time.
+    R = _gpu()
+    N, M, k = 20000, 256, 32
+    xs = [workloads.normal(N, M, seed=84 + i) for i in range(3)]
+    xd = torch.from_numpy(xs[0]).cuda()
+    ov = torch.empty((N, k), dtype=torch.float32, device="cuda")
+    oi = torch.empty((N, k), dtype=torch.int32, device="cuda")
+    sv = torch.empty((N, k), dtype=torch.float32, device="cuda")
+    si = torch.empty((N, k), dtype=torch.int32, device="cuda")
+    R.rtopk_rowwise_exact(xd, k, ov, oi)  # warm-up outside capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        R.rtopk_rowwise_exact(xd, k, ov, oi)
+        R.rtopk_rowwise(xd, k, 6, sv, si)
+    for x in xs + xs[:1]:
+        xd.copy_(torch.from_numpy(x).cuda())
+        ov.fill_(-1.0)
+        oi.fill_(-1)
+        si.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ev, ei = oracle.topk_exact(x, k)
+        _, e2 = oracle.topk_earlystop(x, k, 6)
+        assert np.array_equal(oi.cpu().numpy(), ei) and np.array_equal(bits(ov.cpu().numpy()), bits(ev))
+        assert np.array_equal(si.cpu().numpy(), e2)
+
+
 def test_other_stream():
     R = _gpu()
     x = workloads.normal(5000, 256, seed=83)
