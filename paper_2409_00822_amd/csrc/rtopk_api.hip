@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int kMaxM = 4096;
+constexpr int kMaxM = 8192;
 constexpr int kVersion = 200;  // 0.2.0
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -52,8 +52,8 @@ int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, floa
   hipError_t err;
   if (M > 128 && M % 4 == 0 && aligned(in, 16)) {
     // 128-bit loads; groups per lane rounded up to an instantiated count
-    static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16};
-    int ng = 16;
+    static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+    int ng = 32;
     for (int cand : kNg) {
       if (M <= 256 * cand) {
         ng = cand;
@@ -109,7 +109,7 @@ const char* rtopk_status_string(int status) {
     case RTOPK_ERR_NULL_POINTER: return "null data pointer with N > 0";
     case RTOPK_ERR_BAD_SHAPE: return "bad shape: need N >= 0 and 1 <= k <= M";
     case RTOPK_ERR_BAD_MAX_ITER: return "max_iter must be >= 0";
-    case RTOPK_ERR_M_TOO_LARGE: return "M exceeds the supported row width (4096; 256 for uint8 columns)";
+    case RTOPK_ERR_M_TOO_LARGE: return "M exceeds the supported row width (8192; 256 for uint8 columns)";
     case RTOPK_ERR_MISALIGNED: return "pointer not aligned to its element size";
     case RTOPK_ERR_LAUNCH: return "the HIP runtime refused the launch";
     case RTOPK_ERR_BAD_EPSILON: return "eps_rel must be >= 0";

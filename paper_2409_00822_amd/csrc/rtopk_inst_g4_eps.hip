@@ -19,6 +19,8 @@ hipError_t launch_g4_eps(int ng, bool full, const LaunchArgs& a) {
     case 8: return pick<8>(full, a);
     case 12: return pick<12>(full, a);
     case 16: return pick<16>(full, a);
+    case 24: return pick<24>(full, a);
+    case 32: return pick<32>(full, a);
     default: return hipErrorInvalidValue;
   }
 }

@@ -22,6 +22,8 @@ hipError_t launch_g4_exact(int ng, bool full, bool u8, const LaunchArgs& a) {
     case 8: return pick<8>(full, u8, a);
     case 12: return pick<12>(full, u8, a);
     case 16: return pick<16>(full, u8, a);
+    case 24: return pick<24>(full, u8, a);
+    case 32: return pick<32>(full, u8, a);
     default: return hipErrorInvalidValue;
   }
 }

@@ -25,6 +25,7 @@ static hipError_t pick_mode(int g, int ng, bool full, bool u8, const LaunchArgs&
     case 16: return pick<1, 16, MODE>(full, u8, a);
     case 32: return pick<1, 32, MODE>(full, u8, a);
     case 64: return pick<1, 64, MODE>(full, u8, a);
+    case 128: return pick<1, 128, MODE>(full, u8, a);
     default: return hipErrorInvalidValue;
   }
 }

@@ -283,47 +283,51 @@ __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int 
 // (generated by gen_search_loops.py; same steps as the generic loops in select_row).
 #include "rtopk_search_loops.inc"
 
-// Search and selection for one row held as x[E] (columns past M hold -inf and are never chosen).
+// Search and selection for one row held as xin[E] (lanes past column M hold duplicates of real
+// elements on entry).
 //   MODE: kExact = Algorithm 1 at epsilon = 0, kEarly = Algorithm 2 with max_iter steps,
 //         kEps = Algorithm 1 with epsilon = eps_rel * |max|.
 // Returns the exit iteration of the search loop (kEps only; 0 otherwise): the number of midpoints
 // evaluated when one of them counted exactly k, one more when the loop ended through its guard.
 template <int G, int NG, bool FULL, int MODE>
-__device__ __forceinline__ int select_row(const float (&x)[G * NG], int lane, int M, int k, int max_iter,
+__device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, int M, int k, int max_iter,
                                           float eps_rel, uint2* stage) {
   constexpr int E = G * NG;
   const uint32_t stage_addr = (uint32_t)(uintptr_t)stage;  // LDS byte address
 
-  // Alg. 1 / Alg. 2, first two steps: row minimum and maximum.
+  // Alg. 1 / Alg. 2, first two steps: row minimum and maximum, as max(x) and max(-x) per lane.
+  // (Lanes past M hold copies of the row's first columns here, which changes neither.)
   float mx, nm;
-  {
-    auto for_min = [&](int e) {  // padding columns must not win the minimum
-      const bool valid = FULL || ((e / G) * kWave + lane) * G < M;
-      return valid ? x[e] : __builtin_inff();
-    };
-    if constexpr (E == 1) {
-      mx = x[0];
-      nm = -for_min(0);
-    } else if constexpr (E == 2) {
-      mx = vmax(x[0], x[1]);
-      nm = vmax_nn(for_min(0), for_min(1));
-    } else {
-      mx = vmax3(x[0], x[1], x[2]);
-      nm = vmax3_nnn(for_min(0), for_min(1), for_min(2));
-      int e = 3;
+  if constexpr (E == 1) {
+    mx = xin[0];
+    nm = -xin[0];
+  } else if constexpr (E == 2) {
+    mx = vmax(xin[0], xin[1]);
+    nm = vmax_nn(xin[0], xin[1]);
+  } else {
+    mx = vmax3(xin[0], xin[1], xin[2]);
+    nm = vmax3_nnn(xin[0], xin[1], xin[2]);
+    int e = 3;
 #pragma unroll
-      for (; e + 1 < E; e += 2) {
-        mx = vmax3(mx, x[e], x[e + 1]);
-        nm = vmax3_ann(nm, for_min(e), for_min(e + 1));
-      }
-      if (e < E) {
-        mx = vmax(mx, x[e]);
-        nm = vmax_an(nm, for_min(e));
-      }
+    for (; e + 1 < E; e += 2) {
+      mx = vmax3(mx, xin[e], xin[e + 1]);
+      nm = vmax3_ann(nm, xin[e], xin[e + 1]);
+    }
+    if (e < E) {
+      mx = vmax(mx, xin[e]);
+      nm = vmax_an(nm, xin[e]);
     }
   }
   float lo, hi;
   wave_max_and_negmin(mx, nm, hi, lo);
+
+  // From here on columns past M must never be counted or chosen: -inf is below every threshold.
+  float x[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const bool valid = FULL || ((e / G) * kWave + lane) * G < M;
+    x[e] = valid ? xin[e] : -__builtin_inff();
+  }
 
   constexpr bool ASM = (E == 2 || E == 4 || E == 8);  // hand-scheduled loops exist for these widths
   constexpr bool KEEP = E <= 8;                       // masks of the last step stay in scalar registers
@@ -489,27 +493,25 @@ __global__ void __launch_bounds__(256)
     const float* row = in + (r0 + (rr < nrows ? rr : 0)) * (int64_t)M;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
+      // Lanes whose columns lie past M load the row's first columns instead (in bounds, no branch, so
+      // all loads of the wavefront stay in flight together).  Duplicates of real elements cannot
+      // change the row's minimum or maximum; select_row turns them into -inf before it counts.
       const int col0 = (g * kWave + lane) * G;
-      if (FULL || col0 < M) {
-const V v = load_streaming<G>(row + col0);
-        if constexpr (G == 1) {
-          x[rr][g] = v;
-        } else if constexpr (G == 2) {
-          x[rr][g * 2 + 0] = v.x;
-          x[rr][g * 2 + 1] = v.y;
-        } else {
-          x[rr][g * 4 + 0] = v.x;
-          x[rr][g * 4 + 1] = v.y;
-          x[rr][g * 4 + 2] = v.z;
-          x[rr][g * 4 + 3] = v.w;
-        }
+      const bool valid = FULL || col0 < M;
+      const V v = load_streaming<G>(row + (valid ? col0 : 0));
+      if constexpr (G == 1) {
+        x[rr][g] = v;
+      } else if constexpr (G == 2) {
+        x[rr][g * 2 + 0] = v.x;
+        x[rr][g * 2 + 1] = v.y;
       } else {
-#pragma unroll
-        for (int c = 0; c < G; ++c) x[rr][g * G + c] = -__builtin_inff();
+        x[rr][g * 4 + 0] = v.x;
+        x[rr][g * 4 + 1] = v.y;
+        x[rr][g * 4 + 2] = v.z;
+        x[rr][g * 4 + 3] = v.w;
       }
     }
   }
-
   // Searching and selecting stages, row by row.
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {

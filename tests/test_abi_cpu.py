@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_limits_and_status_strings(lib):
     assert lib.rtopk_version() >= 100
-    assert lib.rtopk_max_m() == 4096
+    assert lib.rtopk_max_m() == 8192
     seen = set()
     for code in range(0, -8, -1):
         s = lib.rtopk_status_string(code)
@@ -60,8 +60,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert f(p, 4, 256, 0, 8, p, p, None) == -2
     assert f(p, 4, 256, 257, 8, p, p, None) == -2
     assert f(p, 4, 256, 32, -1, p, p, None) == -3
-    assert f(p, 4, 4100, 32, 8, p, p, None) == -4
-    assert fe(p, 4, 4100, 32, p, p, None) == -4
+    assert f(p, 4, 8200, 32, 8, p, p, None) == -4
+    assert fe(p, 4, 8200, 32, p, p, None) == -4
     assert lib.rtopk_rowwise_u8(p, 4, 260, 32, 8, p, p, None) == -4
     assert lib.rtopk_rowwise_exact_u8(p, 4, 260, 32, p, p, None) == -4
     fz = lib.rtopk_rowwise_eps
@@ -71,7 +71,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fz(p, 4, 256, 32, float("nan"), p, p, None, None) == -7
     assert fz(p, 0, 256, 32, 0.5, None, None, None, None) == 0
     assert fz(p, 4, 256, 32, 0.5, p, p, p + 2, None) == -5
-    assert fz(p, 4, 4100, 32, 0.5, p, p, None, None) == -4
+    assert fz(p, 4, 8200, 32, 0.5, p, p, None, None) == -4
     assert f(p + 2, 4, 256, 32, 8, p, p, None) == -5
     assert f(p, 4, 256, 32, 8, p + 1, p, None) == -5
     assert f(p, 4, 256, 32, 8, p, p + 2, None) == -5

@@ -63,7 +63,8 @@ SHAPES = [
     (77, 200, (25, 32)), (4099, 256, (1, 16, 31, 32, 64, 128, 255, 256)), (50, 260, (33, 64)),
     (130, 300, (32,)), (515, 512, (64, 100)), (129, 768, (96,)), (40, 1000, (125, 128)),
     (259, 1024, (128, 1000)), (33, 1500, (200,)), (67, 2048, (256,)), (35, 3000, (64,)),
-    (70, 4096, (64, 256, 1024)), (9, 4095, (7, 512)), (17, 1021, (17,)),
+    (70, 4096, (64, 256, 1024)), (9, 4095, (7, 512)), (17, 1021, (17,)), (21, 6000, (300,)),
+    (20, 8192, (64, 512, 4097)), (7, 5001, (33,)), (5, 8191, (8,)),
 ]
 
 
@@ -95,7 +96,7 @@ def test_tie_heavy_rows(M):
                 assert_parity(R, x, k, "early", mi, tag=f"{gen} M={M} k={k} mi={mi}")
 
 
-@pytest.mark.parametrize("M", [1280, 2048, 3000, 4096])
+@pytest.mark.parametrize("M", [1280, 2048, 3000, 4096, 6144, 8192])
 def test_tie_heavy_wide_rows(M):
     # wide rows count without keeping masks and select through the converged-search path under ties
     R = _gpu()
@@ -196,7 +197,8 @@ def assert_eps_parity(R, x_np, k, eps_rel, tag=""):
 
 @pytest.mark.parametrize("N,M,ks", [(9, 7, (1, 3, 7)), (257, 128, (16, 128)), (4099, 256, (1, 32, 128, 256)),
                                      (130, 300, (32,)), (515, 512, (64,)), (129, 768, (96,)), (259, 1024, (128,)),
-                                     (35, 3000, (64,)), (70, 4096, (256,)), (9, 4095, (7,)), (100, 100, (12,))])
+                                     (35, 3000, (64,)), (70, 4096, (256,)), (9, 4095, (7,)), (100, 100, (12,)),
+                                     (12, 8192, (100,)), (6, 7000, (64,))])
 def test_eps_mode_small_shapes(N, M, ks):
     R = _gpu()
     x = workloads.normal(N, M, seed=N * 31 + M)
