@@ -8,6 +8,9 @@ same way and reported in the same JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
+Before the W warm-up steps the kernel is run untimed for about 60 ms (--spinup-ms): after idle the
+GPU needs ~15 ms of work before its clocks settle, and launches in that window take 15-30 % longer.
+
 Prints exactly one JSON line on stdout; progress goes to stderr.
 """
 from __future__ import annotations
@@ -26,6 +29,22 @@ MEASURED_TRAFFIC_BYTES = 1342370645
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def spin_up(torch, fn, ms):
+    """Run `fn` back to back for about `ms` milliseconds of GPU time (untimed)."""
+    if ms <= 0:
+        return
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    per = max(a.elapsed_time(b) / 5.0, 1e-3)
+    for _ in range(int(ms / per) + 1):
+        fn()
+    torch.cuda.synchronize()
 
 
 def time_calls(torch, fn, steps, warmup):
@@ -54,8 +73,11 @@ def time_calls(torch, fn, steps, warmup):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--spinup-ms", type=float, default=60.0,
+                    help="untimed launches run for about this long before the warm-up steps, so that the GPU's "
+                         "clocks have settled: the first ~15 ms after idle run 15-30%% slower")
     ap.add_argument("--workload", default="c1_maxk",
                     help="name in workloads.CONFIGS (default: the headline c1_maxk, N=2^20 x M=256)")
     ap.add_argument("--rows", type=int, default=None, help="override the workload's N")
@@ -107,9 +129,11 @@ def main():
         f_early(x, k, max_iter, out_v, out_i)
 
     log("timing exact mode ...")
+    spin_up(torch, exact, args.spinup_ms)
     wall_e, launch_e = time_calls(torch, exact, args.steps, args.warmup)
     log(f"  exact: {wall_e / args.steps * 1e6:.1f} us/step wall, {launch_e * 1e6:.1f} us/launch (events)")
     log(f"timing early-stop mode (max_iter={max_iter}) ...")
+    spin_up(torch, early, args.spinup_ms / 4)
     wall_s, launch_s = time_calls(torch, early, args.steps, args.warmup)
     log(f"  early: {wall_s / args.steps * 1e6:.1f} us/step wall, {launch_s * 1e6:.1f} us/launch (events)")
 
