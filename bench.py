@@ -24,7 +24,7 @@ import time
 PEAK_HBM_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the exact kernel at the headline shape, from the rocprofv3 --pmc runs summarised
 # in profiles/rtopk_wave_kernel_c1_maxk_pmc.md (not measured live: counters need the profiler).
-MEASURED_TRAFFIC_BYTES = 1342370645
+MEASURED_TRAFFIC_BYTES = 1342419917
 
 
 def log(*a):
