@@ -469,6 +469,18 @@ __device__ __forceinline__ typename VecOf<G>::type load_streaming(const float* p
   }
 }
 
+// 128-bit and 32-bit output stores with the sc1 cache-policy bit (write through at device scope):
+// the outputs are written once and never read back by this kernel; on a streaming probe with this
+// kernel's traffic sc1 stores were ~2 % faster than default ones (non-temporal stores were 12 % slower).
+__device__ __forceinline__ void store_streaming(uint4* p, uint4 v) {
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  const u4 d = {v.x, v.y, v.z, v.w};
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
+}
+__device__ __forceinline__ void store_streaming(uint32_t* p, uint32_t v) {
+  asm volatile("global_store_dword %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+
 template <int G, int NG, int R, bool FULL, int MODE, typename IdxT>
 __global__ void __launch_bounds__(256)
     rtopk_wave_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
@@ -535,11 +547,11 @@ __global__ void __launch_bounds__(256)
     for (int q = lane; q < (total >> 2); q += kWave) {
       const uint4 a = *reinterpret_cast<const uint4*>(stage + 4 * q);
       const uint4 b = *reinterpret_cast<const uint4*>(stage + 4 * q + 2);
-      reinterpret_cast<uint4*>(ov)[q] = make_uint4(a.x, a.z, b.x, b.z);
+      store_streaming(reinterpret_cast<uint4*>(ov) + q, make_uint4(a.x, a.z, b.x, b.z));
       if constexpr (sizeof(IdxT) == 4) {
-        reinterpret_cast<uint4*>(oi)[q] = make_uint4(a.y, a.w, b.y, b.w);
+        store_streaming(reinterpret_cast<uint4*>(oi) + q, make_uint4(a.y, a.w, b.y, b.w));
       } else {
-        reinterpret_cast<uint32_t*>(oi)[q] = a.y | (a.w << 8) | (b.y << 16) | (b.w << 24);
+        store_streaming(reinterpret_cast<uint32_t*>(oi) + q, a.y | (a.w << 8) | (b.y << 16) | (b.w << 24));
       }
     }
   } else {
