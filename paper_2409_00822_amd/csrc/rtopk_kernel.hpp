@@ -581,7 +581,8 @@ hipError_t launch(const LaunchArgs& a) {
   return hipGetLastError();
 }
 
-// Rows per wavefront for E = G*NG registers per row: keep R*E at about 32 VGPRs.
-constexpr int rows_per_wave(int E) { return E <= 4 ? 8 : (E <= 8 ? 4 : (E <= 16 ? 2 : 1)); }
+// Rows per wavefront for E = G*NG registers per row, from sweeps at 2^20 rows: 16 for M <= 128,
+// 8 for M = 256, 2 for M = 512..1024 (M = 512 runs 10 % slower with 4), 1 beyond.
+constexpr int rows_per_wave(int E) { return E <= 2 ? 16 : (E <= 4 ? 8 : (E <= 16 ? 2 : 1)); }
 
 }  // namespace rtopk
