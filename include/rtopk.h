@@ -89,6 +89,18 @@ int rtopk_rowwise_exact_u8(const float* in, int64_t N, int32_t M, int32_t k, flo
 int rtopk_rowwise_eps(const float* in, int64_t N, int32_t M, int32_t k, float eps_rel, float* out_vals,
                       int32_t* out_idx, int32_t* out_iters, void* stream);
 
+/*
+ * The k SMALLEST values per row (Section 3: the row-wise operation finds "the largest (or smallest)
+ * k elements"; the paper develops the largest case without loss of generality).  Defined as the two
+ * operations above applied to the negated row, with the original values written out: Algorithm 2's
+ * thresholds are midpoints of the negated minimum and maximum, counts are of v <= -thres.  Ties go
+ * to the lower column; columns ascend; int32 columns.
+ */
+int rtopk_rowwise_smallest(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
+                           int32_t* out_idx, void* stream);
+int rtopk_rowwise_exact_smallest(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx,
+                                 void* stream);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* rtopk_status_string(int status);
 

@@ -39,6 +39,11 @@ def _load():
         lib.oracle_topk_earlystop_ex.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                                  ctypes.c_int32, ctypes.c_int32, f32p, i32p, i32p]
         lib.oracle_topk_earlystop_ex.restype = ctypes.c_int
+        lib.oracle_topk_exact_smallest.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, f32p, i32p]
+        lib.oracle_topk_exact_smallest.restype = ctypes.c_int
+        lib.oracle_topk_earlystop_smallest.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                       ctypes.c_int32, f32p, i32p]
+        lib.oracle_topk_earlystop_smallest.restype = ctypes.c_int
         lib.oracle_alg1.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                     ctypes.c_int32, f32p, i32p, i32p]
         lib.oracle_alg1.restype = ctypes.c_int
@@ -97,6 +102,28 @@ def topk_earlystop(x: np.ndarray, k: int, max_iter: int, stop_on_equal: bool = F
     if rc != 0:
         raise ValueError("oracle_topk_earlystop: bad arguments")
     return (vals, idx, hit) if return_hit_iter else (vals, idx)
+
+
+def topk_exact_smallest(x: np.ndarray, k: int):
+    """Plain-definition k smallest per row (value ascending, then column ascending), columns ascending."""
+    x = _check_in(x)
+    N, M = x.shape
+    vals = np.empty((N, k), dtype=np.float32)
+    idx = np.empty((N, k), dtype=np.int32)
+    if _load().oracle_topk_exact_smallest(_f32(x), N, M, k, _f32(vals), _i32(idx)) != 0:
+        raise ValueError("oracle_topk_exact_smallest: bad arguments")
+    return vals, idx
+
+
+def topk_earlystop_smallest(x: np.ndarray, k: int, max_iter: int):
+    """Algorithm 2 on the negated row, original values returned."""
+    x = _check_in(x)
+    N, M = x.shape
+    vals = np.empty((N, k), dtype=np.float32)
+    idx = np.empty((N, k), dtype=np.int32)
+    if _load().oracle_topk_earlystop_smallest(_f32(x), N, M, k, max_iter, _f32(vals), _i32(idx)) != 0:
+        raise ValueError("oracle_topk_earlystop_smallest: bad arguments")
+    return vals, idx
 
 
 def alg1(x: np.ndarray, k: int, eps_rel: float = 0.0, collect: int = 1, want_select: bool = True,

@@ -14,6 +14,9 @@
 //                          dyadic inputs, by its reduction to exact top-k, and
 //                          (through the shared loop, stop_on_equal = 1) by the
 //                          Hit and E1 columns of Table 2.
+//   oracle_topk_*_smallest the same two for the k smallest values (Section 3): the plain definition,
+//                          and Algorithm 2 on the negated row.  Pinned by brute-force sorting and by
+//                          the mirror identity smallest(v) = largest(-v).
 //   oracle_alg1            Algorithm 1, step by step, fp32, with the readings
 //                          listed below.  Pinned by Tables 1 and 5 (exit
 //                          iterations), by Eq. 4, and by equality with the
@@ -250,6 +253,45 @@ int oracle_alg1(const float* in, int64_t N, int32_t M, int32_t k, float eps_rel,
       emit(v, M, sel, k, out_vals + r * (int64_t)k, out_idx + r * (int64_t)k);
     }
   }
+  return 0;
+}
+
+// The k SMALLEST values per row (Section 3: "largest (or smallest)").  Exact: the plain definition,
+// pairs ordered by value ascending, then column ascending.
+int oracle_topk_exact_smallest(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx) {
+  if (N < 0 || M < 1 || k < 1 || k > M) return -1;
+  if (N > 0 && (!in || !out_vals || !out_idx)) return -1;
+#pragma omp parallel
+  {
+    std::vector<Pair> p((size_t)M);
+#pragma omp for schedule(static)
+    for (int64_t r = 0; r < N; ++r) {
+      const float* v = in + r * (int64_t)M;
+      for (int32_t i = 0; i < M; ++i) p[i] = Pair{v[i], i};
+      std::nth_element(p.begin(), p.begin() + k, p.end(),
+                       [](const Pair& a, const Pair& b) { return a.v < b.v || (a.v == b.v && a.i < b.i); });
+      std::sort(p.begin(), p.begin() + k, [](const Pair& a, const Pair& b) { return a.i < b.i; });
+      for (int32_t j = 0; j < k; ++j) {
+        out_vals[r * (int64_t)k + j] = p[j].v;
+        out_idx[r * (int64_t)k + j] = p[j].i;
+      }
+    }
+  }
+  return 0;
+}
+
+// Early stopping for the k smallest: Algorithm 2 applied to the negated row ("without loss of
+// generality"), with the original values written out.
+int oracle_topk_earlystop_smallest(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter,
+                                   float* out_vals, int32_t* out_idx) {
+  if (N < 0 || M < 1 || k < 1 || k > M || max_iter < 0) return -1;
+  if (N > 0 && (!in || !out_vals || !out_idx)) return -1;
+  std::vector<float> neg((size_t)N * (size_t)M);
+  for (size_t i = 0; i < neg.size(); ++i) neg[i] = -in[i];
+  const int rc = oracle_topk_earlystop_ex(neg.data(), N, M, k, max_iter, 0, out_vals, out_idx, nullptr);
+  if (rc != 0) return rc;
+  for (int64_t r = 0; r < N; ++r)
+    for (int32_t j = 0; j < k; ++j) out_vals[r * (int64_t)k + j] = in[r * (int64_t)M + out_idx[r * (int64_t)k + j]];
   return 0;
 }
 

@@ -13,6 +13,8 @@ from .rtopk import (  # noqa: F401
     rtopk_rowwise,
     rtopk_rowwise_eps,
     rtopk_rowwise_exact,
+    rtopk_rowwise_exact_smallest,
+    rtopk_rowwise_smallest,
     rtopk_rowwise_exact_u8,
     rtopk_rowwise_u8,
     rtopk_status_string,

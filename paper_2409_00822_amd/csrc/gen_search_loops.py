@@ -18,9 +18,11 @@ import sys
 ELEMS = (2, 4, 8)
 
 
-def count_lines(E, t):
-    """asm lines: masks m0..m{E-1} = (x_e >= t), c0 = total popcount (c1.. are temporaries)."""
-    out = [f'"v_cmp_ge_f32 %[m{e}], %[x{e}], %[{t}]\\n\\t"' for e in range(E)]
+def count_lines(E, t, neg):
+    """asm lines: masks m0..m{E-1} = (key_e >= t), c0 = total popcount (c1.. are temporaries).
+    key = x, or -x (a free source modifier) for the smallest-k variant."""
+    sign = "-" if neg else ""
+    out = [f'"v_cmp_ge_f32 %[m{e}], {sign}%[x{e}], %[{t}]\\n\\t"' for e in range(E)]
     if E == 4:  # balanced tree: shorter dependent chain
         out += [f'"s_bcnt1_i32_b64 %[c{e}], %[m{e}]\\n\\t"' for e in range(4)]
         out += ['"s_add_i32 %[c0], %[c0], %[c1]\\n\\t"', '"s_add_i32 %[c2], %[c2], %[c3]\\n\\t"',
@@ -49,11 +51,11 @@ def emit(lines, outs, ins, indent="      "):
             f'\n{indent}: "vcc", "scc");\n')
 
 
-def gen_exact(E):
+def gen_exact(E, neg):
     L = []
     L += ['// ---- copy B (entry): midpoint in u, no convergence test', '".Lrtopk_b_%=:\\n\\t"',
           '"v_add_f32 %[u], %[lo], %[hi]\\n\\t"', '"v_mul_f32 %[u], 0.5, %[u]\\n\\t"']
-    L += count_lines(E, "u")
+    L += count_lines(E, "u", neg)
     L += ['"s_cmp_lt_i32 %[c0], %[k]\\n\\t"', '"s_cbranch_scc1 .Lrtopk_bless_%=\\n\\t"',
           '"s_cmp_gt_i32 %[c0], %[k]\\n\\t"', '"v_mov_b32 %[lo], %[u]\\n\\t"',
           '"s_cbranch_scc1 .Lrtopk_a_%=\\n\\t"', '"s_branch .Lrtopk_hit_%=\\n\\t"',
@@ -61,7 +63,7 @@ def gen_exact(E):
     L += ['// ---- copy A: midpoint in t, compared with copy B\'s (equal or unordered: converged)',
           '".Lrtopk_a_%=:\\n\\t"', '"v_add_f32 %[t], %[lo], %[hi]\\n\\t"', '"v_mul_f32 %[t], 0.5, %[t]\\n\\t"',
           '"v_cmp_lg_f32 vcc, %[t], %[u]\\n\\t"', '"s_cbranch_vccz .Lrtopk_conv_%=\\n\\t"']
-    L += count_lines(E, "t")
+    L += count_lines(E, "t", neg)
     L += ['"s_cmp_lt_i32 %[c0], %[k]\\n\\t"', '"s_cbranch_scc1 .Lrtopk_aless_%=\\n\\t"',
           '"s_cmp_gt_i32 %[c0], %[k]\\n\\t"', '"v_mov_b32 %[lo], %[t]\\n\\t"',
           '"s_cbranch_scc1 .Lrtopk_b_%=\\n\\t"', '"s_branch .Lrtopk_hit_%=\\n\\t"',
@@ -69,21 +71,21 @@ def gen_exact(E):
           '".Lrtopk_conv_%=:\\n\\t"', '"s_mov_b32 %[hit], 0\\n\\t"', '"s_branch .Lrtopk_end_%=\\n\\t"',
           '".Lrtopk_hit_%=:\\n\\t"', '"s_mov_b32 %[hit], 1\\n\\t"', '".Lrtopk_end_%=:"']
     outs, ins = operands(E, ['[t] "=&v"(t)', '[u] "=&v"(u)', '[hit] "=&s"(hit)'], [])
-    return (f"""// Algorithm 1 at epsilon = 0, {E} values per lane.  Returns true when a step counted exactly k (m[] then
+    return (f"""// Algorithm 1 at epsilon = 0, {E} values per lane{', keys = negated values' if neg else ''}.  Returns true when a step counted exactly k (m[] then
 // selects the answer); false when the search converged first (lo, hi hold the final bounds).  Steps
 // alternate between two code copies that keep their midpoints in different registers, so that copy A
 // can compare its midpoint with the previous one.
 __device__ __forceinline__ bool search_exact_asm(const float (&x)[{E}], float& lo, float& hi, int k,
-                                                 uint64_t (&m)[{E}]) {{
+                                                 uint64_t (&m)[{E}], std::{"true" if neg else "false"}_type /*keys negated*/) {{
   float t, u;
   int c0, c1, c2, c3, hit;
 """ + emit(L, outs, ins) + "  return hit != 0;\n}\n")
 
 
-def gen_early(E):
+def gen_early(E, neg):
     L = ['"s_mov_b32 %[c0], -1\\n\\t"', '"s_sub_u32 %[it], %[n], 1\\n\\t"', '"s_cbranch_scc1 .Lrtopk_end_%=\\n\\t"',
          '".Lrtopk_top_%=:\\n\\t"', '"v_add_f32 %[t], %[lo], %[hi]\\n\\t"', '"v_mul_f32 %[t], 0.5, %[t]\\n\\t"']
-    L += count_lines(E, "t")
+    L += count_lines(E, "t", neg)
     L += ['"s_cmp_lt_i32 %[c0], %[k]\\n\\t"', '"s_cbranch_scc1 .Lrtopk_less_%=\\n\\t"',
           '"s_cmp_gt_i32 %[c0], %[k]\\n\\t"', '"v_mov_b32 %[lo], %[t]\\n\\t"',
           '"s_cbranch_scc0 .Lrtopk_end_%=\\n\\t"', '"s_sub_u32 %[it], %[it], 1\\n\\t"',
@@ -91,11 +93,11 @@ def gen_early(E):
           '".Lrtopk_less_%=:\\n\\t"', '"v_mov_b32 %[hi], %[t]\\n\\t"', '"s_sub_u32 %[it], %[it], 1\\n\\t"',
           '"s_cbranch_scc0 .Lrtopk_top_%=\\n\\t"', '".Lrtopk_end_%=:"']
     outs, ins = operands(E, ['[t] "=&v"(t)', '[it] "=&s"(it)'], ['[n] "s"(max_iter)'])
-    return (f"""// Algorithm 2, {E} values per lane: max_iter steps (fewer when a step counts exactly k, after which the
+    return (f"""// Algorithm 2, {E} values per lane{', keys = negated values' if neg else ''}: max_iter steps (fewer when a step counts exactly k, after which the
 // selection cannot change).  Returns the count of the last step, or -1 when no step ran; when it is
 // >= k, m[] holds the masks of x >= lo.
 __device__ __forceinline__ int search_early_asm(const float (&x)[{E}], float& lo, float& hi, int k, int max_iter,
-                                                uint64_t (&m)[{E}]) {{
+                                                uint64_t (&m)[{E}], std::{"true" if neg else "false"}_type /*keys negated*/) {{
   float t;
   int c0, c1, c2, c3, it;
 """ + emit(L, outs, ins) + "  return c0;\n}\n")
@@ -106,7 +108,8 @@ def main():
     text = ("// GENERATED by gen_search_loops.py -- do not edit by hand.\n"
             "// Hand-scheduled search loops (gfx950 inline assembly); included inside namespace rtopk.\n\n")
     for E in ELEMS:
-        text += gen_exact(E) + "\n" + gen_early(E) + "\n"
+        for neg in (False, True):
+            text += gen_exact(E, neg) + "\n" + gen_early(E, neg) + "\n"
     path = os.path.join(here, "rtopk_search_loops.inc")
     old = open(path).read() if os.path.exists(path) else None
     if old != text:

@@ -10,7 +10,7 @@
 namespace {
 
 constexpr int kMaxM = 8192;
-constexpr int kVersion = 200;  // 0.2.0
+constexpr int kVersion = 300;  // 0.3.0
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -19,7 +19,7 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 //         kEps (Algorithm 1, epsilon = eps_rel * |max|, optional exit-iteration output).
 //   u8:   out_idx is uint8_t[N][k] (requires M <= 256), else int32_t[N][k].
 int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float eps_rel, int mode, float* out_vals,
-        void* out_idx, int32_t* out_iters, bool u8, void* stream) {
+        void* out_idx, int32_t* out_iters, bool u8, void* stream, bool smallest = false) {
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
   if (mode == rtopk::kEarly && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
   if (mode == rtopk::kEps && !(eps_rel >= 0.0f)) return RTOPK_ERR_BAD_EPSILON;
@@ -44,6 +44,7 @@ int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, floa
   a.max_iter = max_iter;
   a.eps_rel = eps_rel;
   a.out_iters = out_iters;
+  a.smallest = smallest;
   a.out_vals = out_vals;
   a.out_idx = out_idx;
   a.vec_store = (k % 4 == 0) && aligned(out_vals, 16) && aligned(out_idx, u8 ? 4 : 16);
@@ -101,6 +102,16 @@ int rtopk_rowwise_exact_u8(const float* in, int64_t N, int32_t M, int32_t k, flo
 int rtopk_rowwise_eps(const float* in, int64_t N, int32_t M, int32_t k, float eps_rel, float* out_vals,
                       int32_t* out_idx, int32_t* out_iters, void* stream) {
   return run(in, N, M, k, 0, eps_rel, rtopk::kEps, out_vals, out_idx, out_iters, false, stream);
+}
+
+int rtopk_rowwise_smallest(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
+                           int32_t* out_idx, void* stream) {
+  return run(in, N, M, k, max_iter, 0.0f, rtopk::kEarly, out_vals, out_idx, nullptr, false, stream, true);
+}
+
+int rtopk_rowwise_exact_smallest(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx,
+                                 void* stream) {
+  return run(in, N, M, k, 0, 0.0f, rtopk::kExact, out_vals, out_idx, nullptr, false, stream, true);
 }
 
 const char* rtopk_status_string(int status) {

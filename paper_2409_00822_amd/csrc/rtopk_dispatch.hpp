@@ -20,6 +20,7 @@ struct LaunchArgs {
   int M, k, max_iter;
   float eps_rel;       // kEps only
   int32_t* out_iters;  // kEps only, may be null
+  bool smallest;       // select the k smallest instead of the k largest (kEarly / kExact, int32 columns)
   float* out_vals;
   void* out_idx;
   int vec_store;  // 1: k % 4 == 0 and both outputs aligned for 128-bit (values) / whole-word (columns) stores

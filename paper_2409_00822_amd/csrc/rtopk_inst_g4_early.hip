@@ -7,7 +7,11 @@ template <int NG>
 static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
   constexpr int R = rows_per_wave(4 * NG);
   if constexpr (NG == 1) {
-    if (u8) return full ? launch<4, NG, R, true, kEarly, uint8_t>(a) : launch<4, NG, R, false, kEarly, uint8_t>(a);
+    if (u8 && !a.smallest) return full ? launch<4, NG, R, true, kEarly, uint8_t>(a) : launch<4, NG, R, false, kEarly, uint8_t>(a);
+  }
+  if (a.smallest) {
+    if (u8) return hipErrorInvalidValue;
+    return full ? launch<4, NG, R, true, kEarly, int32_t, true>(a) : launch<4, NG, R, false, kEarly, int32_t, true>(a);
   }
   return full ? launch<4, NG, R, true, kEarly, int32_t>(a) : launch<4, NG, R, false, kEarly, int32_t>(a);
 }

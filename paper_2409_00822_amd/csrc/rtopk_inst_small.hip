@@ -8,7 +8,13 @@ template <int G, int NG, int MODE>
 static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
   constexpr int R = rows_per_wave(G * NG);
   if constexpr (64 * G * NG <= 256 && MODE != kEps) {
-    if (u8) return full ? launch<G, NG, R, true, MODE, uint8_t>(a) : launch<G, NG, R, false, MODE, uint8_t>(a);
+    if (u8 && !a.smallest) return full ? launch<G, NG, R, true, MODE, uint8_t>(a) : launch<G, NG, R, false, MODE, uint8_t>(a);
+  }
+  if constexpr (MODE != kEps) {
+    if (a.smallest) {
+      if (u8) return hipErrorInvalidValue;
+      return full ? launch<G, NG, R, true, MODE, int32_t, true>(a) : launch<G, NG, R, false, MODE, int32_t, true>(a);
+    }
   }
   return full ? launch<G, NG, R, true, MODE, int32_t>(a) : launch<G, NG, R, false, MODE, int32_t>(a);
 }

@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "rtopk_dispatch.hpp"
 
 namespace rtopk {
@@ -91,6 +93,14 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask, uint32_t add) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, add));
 }
 
+// The search key of a value: the value itself when the k largest are wanted, its negation when the
+// k smallest are (Section 3: "largest (or smallest) ... without loss of generality").  The negation
+// folds into the source modifiers of the compares, so the smallest-k variant costs nothing extra.
+template <bool NEG>
+__device__ __forceinline__ float keyof(float v) {
+  return NEG ? -v : v;
+}
+
 // p + (bit `lane` of mask): one add-with-carry whose carry-in is the lane mask.
 __device__ __forceinline__ uint32_t add_mask_bit(uint32_t p, uint64_t mask) {
   uint32_t r;
@@ -140,12 +150,12 @@ __device__ __forceinline__ void move_bound(float& lo, float& hi, float t, int cn
 
 // cnt = #{e, lane : x[e] >= t}.  The compare writes a 64-lane mask to scalar registers; the count is
 // a scalar popcount, so no cross-lane reduction is needed.  m[e] keeps the masks.
-template <int E>
+template <int E, bool NEG>
 __device__ __forceinline__ int count_ge(const float (&x)[E], float t, uint64_t (&m)[E]) {
   int cnt = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    m[e] = __builtin_amdgcn_ballot_w64(x[e] >= t);
+    m[e] = __builtin_amdgcn_ballot_w64(keyof<NEG>(x[e]) >= t);
     cnt += __builtin_popcountll(m[e]);
   }
   return cnt;
@@ -166,15 +176,15 @@ __device__ __forceinline__ int wave_sum(int v) {
 // scalar instructions per 64 elements, a per-lane accumulation two vector and no scalar ones; wide
 // rows split the elements between the two so that neither unit is the bottleneck (ACC of the E
 // elements are accumulated per lane and reduced once).
-template <int E, int ACC>
+template <int E, int ACC, bool NEG>
 __device__ __forceinline__ int count_ge_wide(const float (&x)[E], float t) {
   int cnt = 0;
 #pragma unroll
-  for (int e = ACC; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= t));
+  for (int e = ACC; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keyof<NEG>(x[e]) >= t));
   if constexpr (ACC > 0) {
     int acc = 0;
 #pragma unroll
-    for (int e = 0; e < ACC; ++e) acc += (x[e] >= t) ? 1 : 0;
+    for (int e = 0; e < ACC; ++e) acc += (keyof<NEG>(x[e]) >= t) ? 1 : 0;
     cnt += wave_sum(acc);
   }
   return cnt;
@@ -185,7 +195,7 @@ __device__ __forceinline__ int count_ge_wide(const float (&x)[E], float t) {
 // pairs to stage[0 ..).  CUT = false promises that there are at most `limit` candidates.
 // LAZY: the masks are not passed in but formed here, group by group, as x >= t, where t is `t_hi`
 // for columns above `split_col` and `t_lo` for columns up to it (a plain threshold has t_lo == t_hi).
-template <int G, int NG, bool CUT, bool LAZY = false>
+template <int G, int NG, bool CUT, bool LAZY, bool NEG>
 __device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const uint64_t* mm, float t_hi, float t_lo,
                                               int split_col, int lane, int limit, uint32_t stage_addr) {
   uint32_t base = 0;  // wave-uniform: candidates in earlier groups
@@ -200,7 +210,7 @@ __device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const ui
     for (int c = 0; c < G; ++c) {
       if constexpr (LAZY) {
         const int col = (g * kWave + ln) * G + c;
-        m[c] = __builtin_amdgcn_ballot_w64(x[g * G + c] >= (col <= split_col ? t_lo : t_hi));
+        m[c] = __builtin_amdgcn_ballot_w64(keyof<NEG>(x[g * G + c]) >= (col <= split_col ? t_lo : t_hi));
       } else {
         m[c] = mm[g * G + c];
       }
@@ -243,7 +253,7 @@ __device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const ui
 
 // Column of the `want`-th (1-based) element, in column order, among those with tb <= x < ta;
 // -1 when want == 0.  Used only after the exact search has converged without cnt == k.
-template <int G, int NG>
+template <int G, int NG, bool NEG>
 __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int lane, float ta, float tb, int want) {
   uint32_t base = 0;  // wave-uniform: band members in earlier groups
   int mine = -1;      // per lane: the wanted column if this lane owns it
@@ -255,7 +265,7 @@ __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int 
     bool b[G];
 #pragma unroll
     for (int c = 0; c < G; ++c) {
-      const float v = x[g * G + c];
+      const float v = keyof<NEG>(x[g * G + c]);
       b[c] = (v >= tb) && !(v >= ta);
       const uint64_t mb = __builtin_amdgcn_ballot_w64(b[c]);
       pos = lanes_below(mb, pos);
@@ -289,7 +299,7 @@ __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int 
 //         kEps = Algorithm 1 with epsilon = eps_rel * |max|.
 // Returns the exit iteration of the search loop (kEps only; 0 otherwise): the number of midpoints
 // evaluated when one of them counted exactly k, one more when the loop ended through its guard.
-template <int G, int NG, bool FULL, int MODE>
+template <int G, int NG, bool FULL, int MODE, bool NEG>
 __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, int M, int k, int max_iter,
                                           float eps_rel, uint2* stage) {
   constexpr int E = G * NG;
@@ -318,15 +328,24 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       nm = vmax_an(nm, xin[e]);
     }
   }
+  // lo, hi bound the keys: for the smallest-k variant the keys are the negated values, whose maximum
+  // is the negated row minimum and vice versa, so the two reduction results just swap roles.
   float lo, hi;
-  wave_max_and_negmin(mx, nm, hi, lo);
+  if constexpr (NEG) {
+    float vmaxv, vminv;
+    wave_max_and_negmin(mx, nm, vmaxv, vminv);
+    hi = -vminv;
+    lo = -vmaxv;
+  } else {
+    wave_max_and_negmin(mx, nm, hi, lo);
+  }
 
-  // From here on columns past M must never be counted or chosen: -inf is below every threshold.
+  // From here on columns past M must never be counted or chosen: a key of -inf is below every threshold.
   float x[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const bool valid = FULL || ((e / G) * kWave + lane) * G < M;
-    x[e] = valid ? xin[e] : -__builtin_inff();
+    x[e] = valid ? xin[e] : (NEG ? __builtin_inff() : -__builtin_inff());  // key -inf
   }
 
   constexpr bool ASM = (E == 2 || E == 4 || E == 8);  // hand-scheduled loops exist for these widths
@@ -337,9 +356,9 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
   uint64_t m[KEEP ? E : 1];
   auto count = [&](float t) -> int {
     if constexpr (KEEP) {
-      return count_ge<E>(x, t, m);
+      return count_ge<E, NEG>(x, t, m);
     } else {
-      return count_ge_wide<E, ACC>(x, t);
+      return count_ge_wide<E, ACC, NEG>(x, t);
     }
   };
   if constexpr (MODE == kExact) {
@@ -350,7 +369,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     bool hit = false;
     float thres = lo;
     if constexpr (ASM) {
-      hit = search_exact_asm(x, lo, hi, k, m);
+      hit = search_exact_asm(x, lo, hi, k, m, std::integral_constant<bool, NEG>());
     } else {
       float seen = lo;
       for (;;) {
@@ -373,14 +392,14 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       }
     }
     if (hit) {
-      compact_masks<G, NG, false, !KEEP>(x, m, thres, thres, -1, lane, k, stage_addr);
+      compact_masks<G, NG, false, !KEEP, NEG>(x, m, thres, thres, -1, lane, k, stage_addr);
     } else {
       // Everything >= hi is taken first (cut at k by column when hi is still the row maximum and k
       // or more tie there); the first k - na members of [lo, hi) follow: all columns up to the
       // (k - na)-th member's column select against lo, the others against hi.
       const int na = count(hi);
-      const int split = nth_column_in_band<G, NG>(x, lane, hi, lo, k - (na < k ? na : k));
-      compact_masks<G, NG, true, true>(x, nullptr, hi, lo, split, lane, k, stage_addr);
+      const int split = nth_column_in_band<G, NG, NEG>(x, lane, hi, lo, k - (na < k ? na : k));
+      compact_masks<G, NG, true, true, NEG>(x, nullptr, hi, lo, split, lane, k, stage_addr);
     }
     return 0;
   } else if constexpr (MODE == kEps) {
@@ -404,17 +423,17 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       move_bound(lo, hi, thres, cnt, k);
     }
     if (hit) {
-      compact_masks<G, NG, false, !KEEP>(x, m, thres, thres, -1, lane, k, stage_addr);
+      compact_masks<G, NG, false, !KEEP, NEG>(x, m, thres, thres, -1, lane, k, stage_addr);
       return steps;
     }
     const int na = count(hi);
-    const int split = nth_column_in_band<G, NG>(x, lane, hi, lo, k - (na < k ? na : k));
-    compact_masks<G, NG, true, true>(x, nullptr, hi, lo, split, lane, k, stage_addr);
+    const int split = nth_column_in_band<G, NG, NEG>(x, lane, hi, lo, k - (na < k ? na : k));
+    compact_masks<G, NG, true, true, NEG>(x, nullptr, hi, lo, split, lane, k, stage_addr);
     return steps + 1;
   } else {
     int cnt = -1;
     if constexpr (ASM) {
-      cnt = search_early_asm(x, lo, hi, k, max_iter, m);
+      cnt = search_early_asm(x, lo, hi, k, max_iter, m, std::integral_constant<bool, NEG>());
     } else {
       for (int it = 0; it < max_iter; ++it) {
         const float thres = (lo + hi) * 0.5f;
@@ -427,9 +446,9 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     }
     if (cnt < k) cnt = count(lo);  // the last step lowered hi (or none ran): the masks are not for lo
     if (cnt == k) {
-      compact_masks<G, NG, false, !KEEP>(x, m, lo, lo, -1, lane, k, stage_addr);
+      compact_masks<G, NG, false, !KEEP, NEG>(x, m, lo, lo, -1, lane, k, stage_addr);
     } else {
-      compact_masks<G, NG, true, !KEEP>(x, m, lo, lo, -1, lane, k, stage_addr);
+      compact_masks<G, NG, true, !KEEP, NEG>(x, m, lo, lo, -1, lane, k, stage_addr);
     }
     return 0;
   }
@@ -481,7 +500,7 @@ __device__ __forceinline__ void store_streaming(uint32_t* p, uint32_t v) {
   asm volatile("global_store_dword %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 
-template <int G, int NG, int R, bool FULL, int MODE, typename IdxT>
+template <int G, int NG, int R, bool FULL, int MODE, bool NEG, typename IdxT>
 __global__ void __launch_bounds__(256)
     rtopk_wave_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
                       float* __restrict__ out_vals, IdxT* __restrict__ out_idx, int32_t* __restrict__ out_iters,
@@ -528,7 +547,7 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
     if (rr < nrows) {
-      const int it = select_row<G, NG, FULL, MODE>(x[rr], lane, M, k, max_iter, eps_rel, stage + (size_t)rr * k);
+      const int it = select_row<G, NG, FULL, MODE, NEG>(x[rr], lane, M, k, max_iter, eps_rel, stage + (size_t)rr * k);
       if constexpr (MODE == kEps) {
         if (out_iters != nullptr && lane == 0) out_iters[r0 + rr] = it;
       }
@@ -566,7 +585,7 @@ __global__ void __launch_bounds__(256)
 
 // ---- host-side launcher -------------------------------------------------------------------------------
 
-template <int G, int NG, int R, bool FULL, int MODE, typename IdxT>
+template <int G, int NG, int R, bool FULL, int MODE, typename IdxT, bool NEG = false>
 hipError_t launch(const LaunchArgs& a) {
   // LDS per wavefront: R*k staged pairs of 8 bytes; at most 64 KiB per block.
   const size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
@@ -575,7 +594,7 @@ hipError_t launch(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((rtopk_wave_kernel<G, NG, R, FULL, MODE, IdxT>), dim3((unsigned)blocks), dim3(waves * kWave),
+  hipLaunchKernelGGL((rtopk_wave_kernel<G, NG, R, FULL, MODE, NEG, IdxT>), dim3((unsigned)blocks), dim3(waves * kWave),
                      per_wave * waves, a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
                      static_cast<IdxT*>(a.out_idx), a.out_iters, a.vec_store);
   return hipGetLastError();

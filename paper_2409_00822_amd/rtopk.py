@@ -31,11 +31,13 @@ def load_library() -> ctypes.CDLL:
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
         lib.rtopk_rowwise.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_u8.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+        lib.rtopk_rowwise_smallest.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+        lib.rtopk_rowwise_exact_smallest.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_exact.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_exact_u8.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_eps.argtypes = [vp, i64, i32, i32, ctypes.c_float, vp, vp, vp, vp]
         for fn in (lib.rtopk_rowwise, lib.rtopk_rowwise_u8, lib.rtopk_rowwise_exact, lib.rtopk_rowwise_exact_u8,
-                   lib.rtopk_rowwise_eps,
+                   lib.rtopk_rowwise_eps, lib.rtopk_rowwise_smallest, lib.rtopk_rowwise_exact_smallest,
                    lib.rtopk_version, lib.rtopk_max_m):
             fn.restype = ctypes.c_int
         lib.rtopk_status_string.argtypes = [ctypes.c_int]
@@ -132,3 +134,23 @@ def rtopk_rowwise_eps(x, k: int, eps_rel: float, out_vals=None, out_idx=None, ou
                                             out_idx.data_ptr(), out_iters.data_ptr() if out_iters is not None else None,
                                             stream))
     return (out_vals, out_idx, out_iters) if out_iters is not None else (out_vals, out_idx)
+
+
+def rtopk_rowwise_smallest(x, k: int, max_iter: int, out_vals=None, out_idx=None):
+    """Algorithm 2 for the k smallest values per row.  Returns (values [N,k] f32, columns [N,k] i32)."""
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.int32)
+    _check(load_library().rtopk_rowwise_smallest(x.data_ptr(), N, M, k, max_iter, out_vals.data_ptr(),
+                                                 out_idx.data_ptr(), stream))
+    return out_vals, out_idx
+
+
+def rtopk_rowwise_exact_smallest(x, k: int, out_vals=None, out_idx=None):
+    """Exact k smallest values per row.  Returns (values [N,k] f32, columns [N,k] i32)."""
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.int32)
+    _check(load_library().rtopk_rowwise_exact_smallest(x.data_ptr(), N, M, k, out_vals.data_ptr(), out_idx.data_ptr(),
+                                                       stream))
+    return out_vals, out_idx

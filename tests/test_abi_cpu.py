@@ -28,7 +28,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert {"rtopk_rowwise", "rtopk_rowwise_exact", "rtopk_rowwise_u8", "rtopk_rowwise_exact_u8", "rtopk_rowwise_eps",
+    assert {"rtopk_rowwise", "rtopk_rowwise_exact", "rtopk_rowwise_u8", "rtopk_rowwise_exact_u8", "rtopk_rowwise_eps", "rtopk_rowwise_smallest", "rtopk_rowwise_exact_smallest",
             "rtopk_status_string", "rtopk_version", "rtopk_max_m"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n

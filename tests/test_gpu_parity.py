@@ -251,6 +251,54 @@ def test_config1_eps_mode_full_size():
     assert_eps_parity(R, x, 32, 0.0, tag="c1 eps=0")
 
 
+# ----------------------------------------------------------------------------------------------
+# the k smallest
+# ----------------------------------------------------------------------------------------------
+def assert_smallest_parity(R, x_np, k, mode, max_iter=0, tag=""):
+    xd = torch.from_numpy(x_np).cuda()
+    if mode == "exact":
+        gv, gi = R.rtopk_rowwise_exact_smallest(xd, k)
+        ov, oi = oracle.topk_exact_smallest(x_np, k)
+    else:
+        gv, gi = R.rtopk_rowwise_smallest(xd, k, max_iter)
+        ov, oi = oracle.topk_earlystop_smallest(x_np, k, max_iter)
+    torch.cuda.synchronize()
+    gi = gi.cpu().numpy()
+    if not np.array_equal(gi, oi):
+        bad = np.nonzero((gi != oi).any(axis=1))[0]
+        raise AssertionError(f"{tag} index mismatch in {bad.size} rows; first {bad[0]}: gpu {gi[bad[0]]} oracle {oi[bad[0]]}")
+    assert np.array_equal(bits(gv.cpu().numpy()), bits(ov)), f"{tag} value bits differ"
+
+
+@pytest.mark.parametrize("N,M,ks", [(9, 7, (1, 3, 7)), (257, 128, (16, 128)), (4099, 256, (1, 32, 128, 256)),
+                                     (130, 300, (32,)), (515, 512, (64,)), (129, 768, (96,)), (259, 1024, (128,)),
+                                     (35, 3000, (64,)), (70, 4096, (256,)), (9, 4095, (7,)), (100, 100, (12,)),
+                                     (12, 8192, (100,)), (33, 63, (8,))])
+def test_smallest_small_shapes(N, M, ks):
+    R = _gpu()
+    x = workloads.normal(N, M, seed=N * 37 + M)
+    for k in ks:
+        assert_smallest_parity(R, x, k, "exact", tag=f"smallest N={N} M={M} k={k}")
+        for mi in (0, 2, 8, 30):
+            assert_smallest_parity(R, x, k, "early", mi, tag=f"smallest N={N} M={M} k={k} mi={mi}")
+
+
+@pytest.mark.parametrize("M", [8, 64, 256, 1024, 4096])
+def test_smallest_tie_heavy_rows(M):
+    R = _gpu()
+    for x in (workloads.from_pool(300, M, 65 + M), workloads.small_ints(300, M, 66 + M, span=4)):
+        for k in sorted({1, max(1, M // 8), M // 2, M}):
+            assert_smallest_parity(R, x, k, "exact", tag=f"smallest ties M={M} k={k}")
+            assert_smallest_parity(R, x, k, "early", 5, tag=f"smallest ties M={M} k={k}")
+
+
+def test_config1_smallest_full_size():
+    R = _gpu()
+    x = workloads.make("c1_maxk")
+    assert_smallest_parity(R, x, 32, "exact", tag="c1 smallest exact")
+    assert_smallest_parity(R, x, 32, "early", 8, tag="c1 smallest early")
+
+
 def test_empty_batch_and_error_codes_on_device():
     R = _gpu()
     x = torch.empty((0, 256), dtype=torch.float32, device="cuda")

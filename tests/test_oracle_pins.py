@@ -319,6 +319,36 @@ def test_mean_overlap_helper_against_python_sets():
 
 
 # --------------------------------------------------------------------------------------------
+# the k smallest (Section 3: "largest (or smallest)")
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("M", [1, 3, 8, 12])
+def test_smallest_matches_bruteforce_and_mirrors_largest(M):
+    x = workloads.from_pool(300, M, seed=300 + M)
+    for k in range(1, M + 1):
+        vals, idx = oracle.topk_exact_smallest(x, k)
+        for r in range(x.shape[0]):
+            order = np.argsort(x[r].astype(np.float64), kind="stable")  # value ascending, column ascending
+            assert np.array_equal(idx[r], np.sort(order[:k]).astype(np.int32)), (M, k, r)
+        assert np.array_equal(bits(vals), bits(np.take_along_axis(x, idx.astype(np.int64), axis=1)))
+        # mirror identity: the k smallest of v are the k largest of -v
+        _, li = oracle.topk_exact(-x, k)
+        assert np.array_equal(li, idx)
+
+
+def test_smallest_earlystop_mirrors_alg2_on_the_negated_row():
+    x = workloads.normal(3000, 256, seed=301)
+    for k, mi in ((32, 0), (32, 4), (32, 8), (100, 6)):
+        sv, si = oracle.topk_earlystop_smallest(x, k, mi)
+        lv, li = oracle.topk_earlystop(-x, k, mi)
+        assert np.array_equal(si, li)
+        assert np.array_equal(bits(sv), bits(-lv))
+    # many steps on distinct values reach the exact answer
+    _, ei = oracle.topk_exact_smallest(x, 32)
+    _, si = oracle.topk_earlystop_smallest(x, 32, 64)
+    assert np.array_equal(si, ei)
+
+
+# --------------------------------------------------------------------------------------------
 # argument checking
 # --------------------------------------------------------------------------------------------
 def test_oracle_rejects_bad_arguments():
