@@ -148,3 +148,35 @@ def mean_overlap(idx_a: np.ndarray, idx_b: np.ndarray) -> float:
     b = np.ascontiguousarray(idx_b, dtype=np.int32)
     assert a.shape == b.shape and a.ndim == 2
     return float(_load().oracle_mean_overlap(_i32(a), _i32(b), a.shape[0], a.shape[1]))
+
+
+# ---------------------------------------------------------------------------------------------
+# 16-bit storage (IEEE half "f16", bfloat16 "bf16").  The paper works in fp32 throughout; for rows
+# stored in 16 bits the selection is DEFINED as the fp32 method applied to the exactly widened row
+# (every half and bfloat16 value is an fp32 value), and the values written out are the row's own
+# 16-bit patterns at the chosen columns.  Inputs and outputs here are raw uint16 bit patterns.
+# ---------------------------------------------------------------------------------------------
+def widen16(bits16: np.ndarray, kind: str) -> np.ndarray:
+    """Exact conversion of uint16 bit patterns to fp32."""
+    b = np.ascontiguousarray(bits16, dtype=np.uint16)
+    if kind == "f16":
+        return b.view(np.float16).astype(np.float32)
+    if kind == "bf16":
+        return (b.astype(np.uint32) << 16).view(np.float32)
+    raise KeyError(kind)
+
+
+def _gather16(bits16: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    return np.take_along_axis(np.ascontiguousarray(bits16, dtype=np.uint16), idx.astype(np.int64), axis=1)
+
+
+def topk_exact_16(bits16: np.ndarray, kind: str, k: int):
+    """Plain-definition top-k of rows stored in 16 bits.  Returns (value bits [N,k] u16, idx [N,k] i32)."""
+    _, idx = topk_exact(widen16(bits16, kind), k)
+    return _gather16(bits16, idx), idx
+
+
+def topk_earlystop_16(bits16: np.ndarray, kind: str, k: int, max_iter: int):
+    """Algorithm 2 in fp32 on the widened row.  Returns (value bits [N,k] u16, idx [N,k] i32)."""
+    _, idx = topk_earlystop(widen16(bits16, kind), k, max_iter)
+    return _gather16(bits16, idx), idx

@@ -17,6 +17,11 @@
 //   oracle_topk_*_smallest the same two for the k smallest values (Section 3): the plain definition,
 //                          and Algorithm 2 on the negated row.  Pinned by brute-force sorting and by
 //                          the mirror identity smallest(v) = largest(-v).
+//   (oracle/__init__.py)   rows stored as IEEE half or bfloat16: the same functions applied to the
+//                          exactly widened row, values returned as the row's own 16-bit patterns.
+//                          Pinned by two independent decoders for the widening, brute force and a
+//                          library top-k for the exact mode, hand traces and the grid
+//                          characterisation for Algorithm 2 (tests/test_oracle_pins_16bit.py).
 //   oracle_alg1            Algorithm 1, step by step, fp32, with the readings
 //                          listed below.  Pinned by Tables 1 and 5 (exit
 //                          iterations), by Eq. 4, and by equality with the

@@ -158,3 +158,27 @@ def make(name: str, N: int | None = None) -> np.ndarray:
     if dist == "laplace":
         return laplace(n, M, seed)
     raise KeyError(dist)
+
+
+# ----------------------------------------------------------------------------
+# 16-bit storage: the same matrices rounded to IEEE half or bfloat16 (round to
+# nearest even), returned as their raw uint16 bit patterns.  Rounding N(0,1)
+# rows to 8 or 11 significant bits makes ties frequent, which is wanted.
+# ----------------------------------------------------------------------------
+def to_f16_bits(x: np.ndarray) -> np.ndarray:
+    with np.errstate(over="ignore"):
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return r.astype(np.uint16)
+
+
+def to_bits16(x: np.ndarray, kind: str) -> np.ndarray:
+    if kind == "f16":
+        return to_f16_bits(x)
+    if kind == "bf16":
+        return to_bf16_bits(x)
+    raise KeyError(kind)
