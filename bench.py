@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--rows", type=int, default=None, help="override the workload's N")
     ap.add_argument("--k", type=int, default=None, help="default: 32 for M=256, else the workload's first k")
     ap.add_argument("--max-iter", type=int, default=8)
+    ap.add_argument("--dtype", default="f32", choices=("f32", "f16", "bf16"),
+                    help="storage type of the rows and of the value output (16-bit types: the same matrix rounded "
+                         "to nearest; the search still runs in fp32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--with-copy", action="store_true",
@@ -112,15 +115,29 @@ def main():
     u8 = cfg["idx"] == "uint8"
     log(f"generating {args.workload} input N={N} M={M} ...")
     x_host = workloads.make(args.workload, N=N)
-    x = torch.from_numpy(x_host).cuda()
-    out_v = torch.empty((N, k), dtype=torch.float32, device="cuda")
+    half = args.dtype != "f32"
+    if half:
+        u8 = False  # the 16-bit entry points write int32 columns
+        tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[args.dtype]
+        x_bits = workloads.to_bits16(x_host, args.dtype)
+        del x_host
+        x = torch.from_numpy(x_bits.view(np.int16)).cuda().view(tdt)
+        out_v = torch.empty((N, k), dtype=tdt, device="cuda")
+    else:
+        x = torch.from_numpy(x_host).cuda()
+        out_v = torch.empty((N, k), dtype=torch.float32, device="cuda")
     out_i = torch.empty((N, k), dtype=torch.uint8 if u8 else torch.int32, device="cuda")
     torch.cuda.synchronize()
 
     # read the row once, write k (value, column) pairs once
-    algo_bytes = N * (4 * M + k * (4 + (1 if u8 else 4)))
-    f_exact = R.rtopk_rowwise_exact_u8 if u8 else R.rtopk_rowwise_exact
-    f_early = R.rtopk_rowwise_u8 if u8 else R.rtopk_rowwise
+    esz = 2 if half else 4
+    algo_bytes = N * (esz * M + k * (esz + (1 if u8 else 4)))
+    if half:
+        f_exact = getattr(R, "rtopk_rowwise_exact_" + args.dtype)
+        f_early = getattr(R, "rtopk_rowwise_" + args.dtype)
+    else:
+        f_exact = R.rtopk_rowwise_exact_u8 if u8 else R.rtopk_rowwise_exact
+        f_early = R.rtopk_rowwise_u8 if u8 else R.rtopk_rowwise
 
     def exact():
         f_exact(x, k, out_v, out_i)
@@ -151,16 +168,25 @@ def main():
         import oracle
     if not args.no_parity:
         log("parity against the CPU oracle on every row ...")
-        ev, ei = oracle.topk_exact(x_host, k)
+        def out_bits():
+            if half:
+                return out_v.view(torch.int16).cpu().numpy().view(np.uint16)
+            return out_v.cpu().numpy().view(np.int32)
+
+        if half:
+            ev, ei = oracle.topk_exact_16(x_bits, args.dtype, k)
+            sv, si = oracle.topk_earlystop_16(x_bits, args.dtype, k, max_iter)
+        else:
+            ev, ei = oracle.topk_exact(x_host, k)
+            sv, si = oracle.topk_earlystop(x_host, k, max_iter)
+            ev, sv = ev.view(np.int32), sv.view(np.int32)
         exact()
         torch.cuda.synchronize()
-        ok_e = bool(np.array_equal(out_i.cpu().numpy().astype(np.int32), ei)
-                    and np.array_equal(out_v.cpu().numpy().view(np.int32), ev.view(np.int32)))
-        sv, si = oracle.topk_earlystop(x_host, k, max_iter)
+        ok_e = bool(np.array_equal(out_i.cpu().numpy().astype(np.int32), ei) and np.array_equal(out_bits(), ev))
         early()
         torch.cuda.synchronize()
         gi = out_i.cpu().numpy().astype(np.int32)
-        ok_s = bool(np.array_equal(gi, si) and np.array_equal(out_v.cpu().numpy().view(np.int32), sv.view(np.int32)))
+        ok_s = bool(np.array_equal(gi, si) and np.array_equal(out_bits(), sv))
         parity = {"exact": ok_e, "early_stop": ok_s}
         recall = oracle.mean_overlap(gi, ei)
         log(f"  parity {parity}, early-stop recall vs exact {recall:.4f}")
@@ -169,7 +195,10 @@ def main():
         reps = []
         for _ in range(9):
             t0 = time.perf_counter()
-            oracle.topk_exact(x_host, k)
+            if half:
+                oracle.topk_exact_16(x_bits, args.dtype, k)
+            else:
+                oracle.topk_exact(x_host, k)
             reps.append(time.perf_counter() - t0)
         t_cpu = statistics.median(reps[1:])
         cpu = {"value": N / t_cpu, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
@@ -178,7 +207,8 @@ def main():
 
     rows_per_s = N * args.steps / wall_e
     result = {
-        "metric": "rows/sec, row top-k N=%d M=%d k=%d fp32, exact mode (early-stop alongside)" % (N, M, k),
+        "metric": "rows/sec, row top-k N=%d M=%d k=%d %s, exact mode (early-stop alongside)"
+                  % (N, M, k, {"f32": "fp32", "f16": "fp16 rows (fp32 search)", "bf16": "bf16 rows (fp32 search)"}[args.dtype]),
         "value": rows_per_s,
         "unit": "rows/s",
         "n_gpus": 1,
@@ -190,15 +220,15 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: N=%d x M=%d fp32, %s, seed %d" % (args.workload, N, M, cfg["dist"], cfg["seed"]),
-                   "k": k, "mode": "exact", "index_type": cfg["idx"]},
+        "config": {"workload": "%s: N=%d x M=%d %s, %s, seed %d" % (args.workload, N, M, args.dtype, cfg["dist"], cfg["seed"]),
+                   "k": k, "mode": "exact", "index_type": "uint8" if u8 else "int32"},
         "early_stop": {"max_iter": max_iter, "rows_per_s": N * args.steps / wall_s,
                        "ms_per_step": wall_s / args.steps * 1e3,
                        "hbm_gbps": algo_bytes / launch_s / 1e9, "recall_vs_exact": recall},
         "parity_vs_oracle": parity,
         "roofline": {"bound": "hbm", "achieved": algo_bytes / launch_e / 1e9, "peak": PEAK_HBM_GBPS,
                      "unit": "GB/s", "frac": algo_bytes / launch_e / 1e9 / PEAK_HBM_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES if (args.workload, N, k) == ("c1_maxk", 1 << 20, 32) else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES if (args.workload, N, k, args.dtype) == ("c1_maxk", 1 << 20, 32, "f32") else None,
                      "traffic_source": "profiles/rtopk_wave_kernel_c1_maxk_pmc.md (FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
                      "kernel": "rtopk_wave_kernel, exact mode, M=%d" % M,
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": launch_e * 1e6},

@@ -101,6 +101,23 @@ int rtopk_rowwise_smallest(const float* in, int64_t N, int32_t M, int32_t k, int
 int rtopk_rowwise_exact_smallest(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx,
                                  void* stream);
 
+/*
+ * Rows stored in 16 bits: IEEE half (_f16) or bfloat16 (_bf16), passed as raw uint16_t bit patterns.
+ * The paper's method is defined in fp32 (Section 3.1); here each row is widened exactly to fp32 as
+ * it is loaded and Algorithm 2 / Algorithm 1 (epsilon = 0) run on the widened row, with fp32
+ * midpoints.  `in` is [N][M] and `out_vals` is [N][k], both 16-bit and 2-byte aligned (fastest when
+ * `in` is 16-byte aligned and M is a multiple of 8); out_vals[r][j] is the bit pattern of
+ * in[r][out_idx[r][j]].  Everything else is as for rtopk_rowwise / rtopk_rowwise_exact.
+ */
+int rtopk_rowwise_f16(const uint16_t* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, uint16_t* out_vals,
+                      int32_t* out_idx, void* stream);
+int rtopk_rowwise_exact_f16(const uint16_t* in, int64_t N, int32_t M, int32_t k, uint16_t* out_vals, int32_t* out_idx,
+                            void* stream);
+int rtopk_rowwise_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, uint16_t* out_vals,
+                       int32_t* out_idx, void* stream);
+int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k, uint16_t* out_vals,
+                             int32_t* out_idx, void* stream);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* rtopk_status_string(int status);
 

@@ -11,6 +11,10 @@ from .rtopk import (  # noqa: F401
     load_library,
     rtopk_max_m,
     rtopk_rowwise,
+    rtopk_rowwise_bf16,
+    rtopk_rowwise_exact_bf16,
+    rtopk_rowwise_exact_f16,
+    rtopk_rowwise_f16,
     rtopk_rowwise_eps,
     rtopk_rowwise_exact,
     rtopk_rowwise_exact_smallest,

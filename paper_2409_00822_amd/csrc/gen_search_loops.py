@@ -51,18 +51,31 @@ def emit(lines, outs, ins, indent="      "):
             f'\n{indent}: "vcc", "scc");\n')
 
 
-def gen_exact(E, neg):
+# Exact mode on rows stored in 16 bits: each midpoint is truncated to the row type's precision (its low
+# 16 fp32 bits cleared for bfloat16, its low 13 for half).  Every element value has those bits clear,
+# so once lo and hi are neighbours on that coarser grid all elements in [lo, hi) are one value, the
+# midpoint repeats and the search ends -- after ~10-14 steps instead of the ~26 it takes to reach fp32
+# resolution, on the many rows whose k-th and (k+1)-th values tie after rounding to 16 bits.
+TRUNC = {0: None, 1: "0xffffe000", 2: "0xffff0000"}  # keyed by rtopk::DType
+
+
+def gen_exact(E, neg, dt=0):
+    tr = TRUNC[dt]
     L = []
     L += ['// ---- copy B (entry): midpoint in u, no convergence test', '".Lrtopk_b_%=:\\n\\t"',
           '"v_add_f32 %[u], %[lo], %[hi]\\n\\t"', '"v_mul_f32 %[u], 0.5, %[u]\\n\\t"']
+    if tr:
+        L += [f'"v_and_b32 %[u], {tr}, %[u]\\n\\t"']
     L += count_lines(E, "u", neg)
     L += ['"s_cmp_lt_i32 %[c0], %[k]\\n\\t"', '"s_cbranch_scc1 .Lrtopk_bless_%=\\n\\t"',
           '"s_cmp_gt_i32 %[c0], %[k]\\n\\t"', '"v_mov_b32 %[lo], %[u]\\n\\t"',
           '"s_cbranch_scc1 .Lrtopk_a_%=\\n\\t"', '"s_branch .Lrtopk_hit_%=\\n\\t"',
           '".Lrtopk_bless_%=:\\n\\t"', '"v_mov_b32 %[hi], %[u]\\n\\t"']
     L += ['// ---- copy A: midpoint in t, compared with copy B\'s (equal or unordered: converged)',
-          '".Lrtopk_a_%=:\\n\\t"', '"v_add_f32 %[t], %[lo], %[hi]\\n\\t"', '"v_mul_f32 %[t], 0.5, %[t]\\n\\t"',
-          '"v_cmp_lg_f32 vcc, %[t], %[u]\\n\\t"', '"s_cbranch_vccz .Lrtopk_conv_%=\\n\\t"']
+          '".Lrtopk_a_%=:\\n\\t"', '"v_add_f32 %[t], %[lo], %[hi]\\n\\t"', '"v_mul_f32 %[t], 0.5, %[t]\\n\\t"']
+    if tr:
+        L += [f'"v_and_b32 %[t], {tr}, %[t]\\n\\t"']
+    L += ['"v_cmp_lg_f32 vcc, %[t], %[u]\\n\\t"', '"s_cbranch_vccz .Lrtopk_conv_%=\\n\\t"']
     L += count_lines(E, "t", neg)
     L += ['"s_cmp_lt_i32 %[c0], %[k]\\n\\t"', '"s_cbranch_scc1 .Lrtopk_aless_%=\\n\\t"',
           '"s_cmp_gt_i32 %[c0], %[k]\\n\\t"', '"v_mov_b32 %[lo], %[t]\\n\\t"',
@@ -71,12 +84,14 @@ def gen_exact(E, neg):
           '".Lrtopk_conv_%=:\\n\\t"', '"s_mov_b32 %[hit], 0\\n\\t"', '"s_branch .Lrtopk_end_%=\\n\\t"',
           '".Lrtopk_hit_%=:\\n\\t"', '"s_mov_b32 %[hit], 1\\n\\t"', '".Lrtopk_end_%=:"']
     outs, ins = operands(E, ['[t] "=&v"(t)', '[u] "=&v"(u)', '[hit] "=&s"(hit)'], [])
-    return (f"""// Algorithm 1 at epsilon = 0, {E} values per lane{', keys = negated values' if neg else ''}.  Returns true when a step counted exactly k (m[] then
+    what = {0: "", 1: ", half rows (midpoints truncated to 11 bits)", 2: ", bfloat16 rows (midpoints truncated to 8 bits)"}[dt]
+    return (f"""// Algorithm 1 at epsilon = 0, {E} values per lane{', keys = negated values' if neg else ''}{what}.  Returns true when a step counted exactly k (m[] then
 // selects the answer); false when the search converged first (lo, hi hold the final bounds).  Steps
 // alternate between two code copies that keep their midpoints in different registers, so that copy A
 // can compare its midpoint with the previous one.
 __device__ __forceinline__ bool search_exact_asm(const float (&x)[{E}], float& lo, float& hi, int k,
-                                                 uint64_t (&m)[{E}], std::{"true" if neg else "false"}_type /*keys negated*/) {{
+                                                 uint64_t (&m)[{E}], std::{"true" if neg else "false"}_type /*keys negated*/,
+                                                 std::integral_constant<int, {dt}> /*row element type*/) {{
   float t, u;
   int c0, c1, c2, c3, hit;
 """ + emit(L, outs, ins) + "  return hit != 0;\n}\n")
@@ -110,6 +125,8 @@ def main():
     for E in ELEMS:
         for neg in (False, True):
             text += gen_exact(E, neg) + "\n" + gen_early(E, neg) + "\n"
+        for dt in (1, 2):
+            text += gen_exact(E, False, dt) + "\n"
     path = os.path.join(here, "rtopk_search_loops.inc")
     old = open(path).read() if os.path.exists(path) else None
     if old != text:

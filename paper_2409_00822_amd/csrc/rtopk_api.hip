@@ -10,7 +10,7 @@
 namespace {
 
 constexpr int kMaxM = 8192;
-constexpr int kVersion = 300;  // 0.3.0
+constexpr int kVersion = 400;  // 0.4.0
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -18,15 +18,17 @@ inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintp
 //   mode: rtopk::kEarly (Algorithm 2, max_iter steps), kExact (Algorithm 1, epsilon = 0) or
 //         kEps (Algorithm 1, epsilon = eps_rel * |max|, optional exit-iteration output).
 //   u8:   out_idx is uint8_t[N][k] (requires M <= 256), else int32_t[N][k].
-int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float eps_rel, int mode, float* out_vals,
-        void* out_idx, int32_t* out_iters, bool u8, void* stream, bool smallest = false) {
+//   dtype: element type of `in` and `out_vals` (rtopk::kF32, kF16, kBF16).
+int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float eps_rel, int mode, void* out_vals,
+        void* out_idx, int32_t* out_iters, bool u8, void* stream, bool smallest = false, int dtype = rtopk::kF32) {
+  const uintptr_t esz = dtype == rtopk::kF32 ? 4 : 2;
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
   if (mode == rtopk::kEarly && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
   if (mode == rtopk::kEps && !(eps_rel >= 0.0f)) return RTOPK_ERR_BAD_EPSILON;
   if (M > kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
   if (N == 0) return RTOPK_OK;
   if (!in || !out_vals || !out_idx) return RTOPK_ERR_NULL_POINTER;
-  if (!aligned(in, 4) || !aligned(out_vals, 4) || (!u8 && !aligned(out_idx, 4)) || !aligned(out_iters, 4))
+  if (!aligned(in, esz) || !aligned(out_vals, esz) || (!u8 && !aligned(out_idx, 4)) || !aligned(out_iters, 4))
     return RTOPK_ERR_MISALIGNED;
 
   // k == M: every column is selected.  Algorithm 2 with zero steps returns the first k columns,
@@ -47,11 +49,35 @@ int run(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, floa
   a.smallest = smallest;
   a.out_vals = out_vals;
   a.out_idx = out_idx;
-  a.vec_store = (k % 4 == 0) && aligned(out_vals, 16) && aligned(out_idx, u8 ? 4 : 16);
+  a.vec_store = (k % 4 == 0) && aligned(out_vals, 4 * esz) && aligned(out_idx, u8 ? 4 : 16);
   a.stream = static_cast<hipStream_t>(stream);
 
   hipError_t err;
-  if (M > 128 && M % 4 == 0 && aligned(in, 16)) {
+  if (dtype != rtopk::kF32) {
+    // 16-bit rows: the widest load whose 64 lanes the row still fills, else the scalar-load fallback
+    int g = 1, ng = 1;
+    bool full = false;
+    if (M > 256 && M % 8 == 0 && aligned(in, 16)) {
+      static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16};
+      g = 8;
+      ng = 16;
+      for (int cand : kNg) {
+        if (M <= 512 * cand) {
+          ng = cand;
+          break;
+        }
+      }
+    } else if (M > 128 && M <= 256 && M % 4 == 0 && aligned(in, 8)) {
+      g = 4;
+    } else if (M > 64 && M <= 128 && M % 2 == 0 && aligned(in, 4)) {
+      g = 2;
+    } else {
+      while (64 * ng < M) ng <<= 1;
+    }
+    full = (M == 64 * g * ng);
+    err = mode == rtopk::kExact ? rtopk::launch_h16_exact(dtype, g, ng, full, a)
+                                : rtopk::launch_h16_early(dtype, g, ng, full, a);
+  } else if (M > 128 && M % 4 == 0 && aligned(in, 16)) {
     // 128-bit loads; groups per lane rounded up to an instantiated count
     static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
     int ng = 32;
@@ -112,6 +138,27 @@ int rtopk_rowwise_smallest(const float* in, int64_t N, int32_t M, int32_t k, int
 int rtopk_rowwise_exact_smallest(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx,
                                  void* stream) {
   return run(in, N, M, k, 0, 0.0f, rtopk::kExact, out_vals, out_idx, nullptr, false, stream, true);
+}
+
+int rtopk_rowwise_f16(const uint16_t* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, uint16_t* out_vals,
+                      int32_t* out_idx, void* stream) {
+  return run(in, N, M, k, max_iter, 0.0f, rtopk::kEarly, out_vals, out_idx, nullptr, false, stream, false, rtopk::kF16);
+}
+
+int rtopk_rowwise_exact_f16(const uint16_t* in, int64_t N, int32_t M, int32_t k, uint16_t* out_vals, int32_t* out_idx,
+                            void* stream) {
+  return run(in, N, M, k, 0, 0.0f, rtopk::kExact, out_vals, out_idx, nullptr, false, stream, false, rtopk::kF16);
+}
+
+int rtopk_rowwise_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, uint16_t* out_vals,
+                       int32_t* out_idx, void* stream) {
+  return run(in, N, M, k, max_iter, 0.0f, rtopk::kEarly, out_vals, out_idx, nullptr, false, stream, false,
+             rtopk::kBF16);
+}
+
+int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k, uint16_t* out_vals,
+                             int32_t* out_idx, void* stream) {
+  return run(in, N, M, k, 0, 0.0f, rtopk::kExact, out_vals, out_idx, nullptr, false, stream, false, rtopk::kBF16);
 }
 
 const char* rtopk_status_string(int status) {

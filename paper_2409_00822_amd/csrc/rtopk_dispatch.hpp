@@ -14,14 +14,21 @@ enum Mode : int {
   kEps = 2     // Algorithm 1 with epsilon = eps_rel * |max|, optional exit-iteration output
 };
 
+// Element type of the input matrix and of the value output.
+enum DType : int {
+  kF32 = 0,
+  kF16 = 1,  // IEEE half
+  kBF16 = 2  // bfloat16
+};
+
 struct LaunchArgs {
-  const float* in;
+  const void* in;
   int64_t N;
   int M, k, max_iter;
   float eps_rel;       // kEps only
   int32_t* out_iters;  // kEps only, may be null
   bool smallest;       // select the k smallest instead of the k largest (kEarly / kExact, int32 columns)
-  float* out_vals;
+  void* out_vals;
   void* out_idx;
   int vec_store;  // 1: k % 4 == 0 and both outputs aligned for 128-bit (values) / whole-word (columns) stores
   hipStream_t stream;
@@ -32,6 +39,10 @@ struct LaunchArgs {
 hipError_t launch_g4_exact(int ng, bool full, bool u8, const LaunchArgs& a);
 hipError_t launch_g4_early(int ng, bool full, bool u8, const LaunchArgs& a);
 hipError_t launch_g4_eps(int ng, bool full, const LaunchArgs& a);  // int32 columns only
+// Rows stored in 16 bits (dtype kF16 or kBF16; kEarly / kExact, int32 columns).  g = elements per load
+// (8, 4, 2 or 1: M % g == 0 and `in` aligned to 2*g bytes), ng = loads per lane (M <= 64*g*ng).
+hipError_t launch_h16_exact(int dtype, int g, int ng, bool full, const LaunchArgs& a);
+hipError_t launch_h16_early(int dtype, int g, int ng, bool full, const LaunchArgs& a);
 // Narrow rows and scalar-load fallback (any M, 4-byte alignment).
 hipError_t launch_small(int g, int ng, bool full, int mode, bool u8, const LaunchArgs& a);
 

@@ -218,20 +218,25 @@ __device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const ui
     uint32_t pos = base;
 #pragma unroll
     for (int c = 0; c < G; ++c) pos = lanes_below(m[c], pos);
-    if constexpr (G == 4) {
-      uint64_t mk[4];
-      uint32_t addr[4], col[4];
-      float val[4];
+    if constexpr (G % 4 == 0) {
+      // four elements at a time: one EXEC restore per four staged pairs
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        mk[c] = m[c];
-        if constexpr (CUT) mk[c] &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
-        addr[c] = stage_addr + pos * 8u;
-        val[c] = x[g * 4 + c];
-        col[c] = (uint32_t)((g * kWave + ln) * 4 + c);
-        if (c + 1 < 4) pos = add_mask_bit(pos, m[c]);
+      for (int h = 0; h < G / 4; ++h) {
+        uint64_t mk[4];
+        uint32_t addr[4], col[4];
+        float val[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int cc = h * 4 + c;
+          mk[c] = m[cc];
+          if constexpr (CUT) mk[c] &= __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit);
+          addr[c] = stage_addr + pos * 8u;
+          val[c] = x[g * G + cc];
+          col[c] = (uint32_t)((g * kWave + ln) * G + cc);
+          if (cc + 1 < G) pos = add_mask_bit(pos, m[cc]);
+        }
+        lds_store_pairs_masked4(mk, addr, val, col);
       }
-      lds_store_pairs_masked4(mk, addr, val, col);
     } else {
 #pragma unroll
       for (int c = 0; c < G; ++c) {
@@ -299,7 +304,19 @@ __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int 
 //         kEps = Algorithm 1 with epsilon = eps_rel * |max|.
 // Returns the exit iteration of the search loop (kEps only; 0 otherwise): the number of midpoints
 // evaluated when one of them counted exactly k, one more when the loop ended through its guard.
-template <int G, int NG, bool FULL, int MODE, bool NEG>
+// Exact mode on rows stored in 16 bits: the midpoint with the fp32 bits below the row type's precision
+// cleared (see gen_search_loops.py for why this ends the search early and is still exact).
+template <int DT>
+__device__ __forceinline__ float midpoint_exact(float lo, float hi) {
+  const float t = (lo + hi) * 0.5f;
+  if constexpr (DT == kF32) {
+    return t;
+  } else {
+    return __uint_as_float(__float_as_uint(t) & (DT == kBF16 ? 0xffff0000u : 0xffffe000u));
+  }
+}
+
+template <int G, int NG, bool FULL, int MODE, bool NEG, int DT = kF32>
 __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, int M, int k, int max_iter,
                                           float eps_rel, uint2* stage) {
   constexpr int E = G * NG;
@@ -369,11 +386,11 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     bool hit = false;
     float thres = lo;
     if constexpr (ASM) {
-      hit = search_exact_asm(x, lo, hi, k, m, std::integral_constant<bool, NEG>());
+      hit = search_exact_asm(x, lo, hi, k, m, std::integral_constant<bool, NEG>(), std::integral_constant<int, DT>());
     } else {
       float seen = lo;
       for (;;) {
-        thres = (lo + hi) * 0.5f;
+        thres = midpoint_exact<DT>(lo, hi);
         if (!(thres < seen || thres > seen)) break;
         seen = thres;
         int cnt = count(thres);
@@ -382,7 +399,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
           break;
         }
         move_bound(lo, hi, thres, cnt, k);
-        thres = (lo + hi) * 0.5f;
+        thres = midpoint_exact<DT>(lo, hi);
         cnt = count(thres);
         if (cnt == k) {
           hit = true;
@@ -456,35 +473,79 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
 
 // ---- kernel -----------------------------------------------------------------------------------------
 
-template <int G>
-struct VecOf;
-template <>
-struct VecOf<1> {
-  using type = float;
-};
-template <>
-struct VecOf<2> {
-  using type = float2;
-};
-template <>
-struct VecOf<4> {
-  using type = float4;
-};
-
-// One G-wide load with the non-temporal hint: every input byte is read exactly once, and keeping it
-// out of the caches' retention policy measurably raises the streaming rate.
-template <int G>
-__device__ __forceinline__ typename VecOf<G>::type load_streaming(const float* p) {
-  if constexpr (G == 1) {
-    return __builtin_nontemporal_load(p);
-  } else if constexpr (G == 2) {
-    typedef float f2 __attribute__((ext_vector_type(2)));
-    const f2 v = __builtin_nontemporal_load(reinterpret_cast<const f2*>(p));
-    return make_float2(v.x, v.y);
+// Element types of the input matrix.  Rows stored in 16 bits are widened exactly to fp32 as they are
+// loaded; the whole method (Section 3.1) then runs in fp32, as the paper defines it, and the values
+// written out are narrowed back, which is exact because they are copies of inputs.
+template <int DT>
+__device__ __forceinline__ float widen_half(uint32_t w, int upper) {  // one of the two 16-bit halves of w
+  if constexpr (DT == kBF16) {
+    return __uint_as_float(upper ? (w & 0xffff0000u) : (w << 16));
   } else {
-    typedef float f4 __attribute__((ext_vector_type(4)));
-    const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
-    return make_float4(v.x, v.y, v.z, v.w);
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)(upper ? (w >> 16) : (w & 0xffffu)));
+  }
+}
+template <int DT>
+__device__ __forceinline__ uint32_t narrow_bits(uint32_t fbits) {  // fp32 bits -> the 16-bit pattern it came from
+  if constexpr (DT == kBF16) {
+    return fbits >> 16;
+  } else {
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)__uint_as_float(fbits));
+  }
+}
+
+// One load of G consecutive elements starting at element `col` of the row at `row` (G*4 bytes for
+// fp32, G*2 bytes for 16-bit types; the address is aligned to that size), with the non-temporal
+// hint: every input byte is read exactly once, and keeping it out of the caches' retention policy
+// measurably raises the streaming rate.
+template <int DT, int G>
+__device__ __forceinline__ void load_group(const typename std::conditional<DT == kF32, float, uint16_t>::type* row,
+                                           int col, float (&dst)[G]) {
+  typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  if constexpr (DT == kF32) {
+    const float* p = row + col;
+    if constexpr (G == 1) {
+      dst[0] = __builtin_nontemporal_load(p);
+    } else if constexpr (G == 2) {
+      typedef float f2 __attribute__((ext_vector_type(2)));
+      const f2 v = __builtin_nontemporal_load(reinterpret_cast<const f2*>(p));
+      dst[0] = v.x;
+      dst[1] = v.y;
+    } else {
+      static_assert(G == 4, "fp32 rows load 1, 2 or 4 values at a time");
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+      dst[0] = v.x;
+      dst[1] = v.y;
+      dst[2] = v.z;
+      dst[3] = v.w;
+    }
+  } else {
+    const uint16_t* p = row + col;
+    if constexpr (G == 1) {
+      dst[0] = widen_half<DT>((uint32_t)__builtin_nontemporal_load(p), 0);
+    } else if constexpr (G == 2) {
+      const uint32_t w = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+      dst[0] = widen_half<DT>(w, 0);
+      dst[1] = widen_half<DT>(w, 1);
+    } else if constexpr (G == 4) {
+      const u2 w = __builtin_nontemporal_load(reinterpret_cast<const u2*>(p));
+      dst[0] = widen_half<DT>(w.x, 0);
+      dst[1] = widen_half<DT>(w.x, 1);
+      dst[2] = widen_half<DT>(w.y, 0);
+      dst[3] = widen_half<DT>(w.y, 1);
+    } else {
+      static_assert(G == 8, "16-bit rows load 1, 2, 4 or 8 values at a time");
+      const u4 w = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
+      dst[0] = widen_half<DT>(w.x, 0);
+      dst[1] = widen_half<DT>(w.x, 1);
+      dst[2] = widen_half<DT>(w.y, 0);
+      dst[3] = widen_half<DT>(w.y, 1);
+      dst[4] = widen_half<DT>(w.z, 0);
+      dst[5] = widen_half<DT>(w.z, 1);
+      dst[6] = widen_half<DT>(w.w, 0);
+      dst[7] = widen_half<DT>(w.w, 1);
+    }
   }
 }
 
@@ -496,16 +557,22 @@ __device__ __forceinline__ void store_streaming(uint4* p, uint4 v) {
   const u4 d = {v.x, v.y, v.z, v.w};
   asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
 }
+__device__ __forceinline__ void store_streaming(uint2* p, uint2 v) {
+  typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+  const u2 d = {v.x, v.y};
+  asm volatile("global_store_dwordx2 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
+}
 __device__ __forceinline__ void store_streaming(uint32_t* p, uint32_t v) {
   asm volatile("global_store_dword %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 
-template <int G, int NG, int R, bool FULL, int MODE, bool NEG, typename IdxT>
+template <int G, int NG, int R, bool FULL, int MODE, bool NEG, typename IdxT, int DT>
 __global__ void __launch_bounds__(256)
-    rtopk_wave_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
-                      float* __restrict__ out_vals, IdxT* __restrict__ out_idx, int32_t* __restrict__ out_iters,
+    rtopk_wave_kernel(const void* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
+                      void* __restrict__ out_vals, IdxT* __restrict__ out_idx, int32_t* __restrict__ out_iters,
                       int vec_store) {
   constexpr int E = G * NG;
+  using ElemT = typename std::conditional<DT == kF32, float, uint16_t>::type;
   extern __shared__ uint2 stage_all[];  // [waves per block][R * k] (value bits, column)
 
   const int lane = threadIdx.x & (kWave - 1);
@@ -518,10 +585,9 @@ __global__ void __launch_bounds__(256)
 
   // Loading stage: all R rows' loads are issued before any is consumed.
   float x[R][E];
-  using V = typename VecOf<G>::type;
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
-    const float* row = in + (r0 + (rr < nrows ? rr : 0)) * (int64_t)M;
+    const ElemT* row = static_cast<const ElemT*>(in) + (r0 + (rr < nrows ? rr : 0)) * (int64_t)M;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       // Lanes whose columns lie past M load the row's first columns instead (in bounds, no branch, so
@@ -529,25 +595,18 @@ __global__ void __launch_bounds__(256)
       // change the row's minimum or maximum; select_row turns them into -inf before it counts.
       const int col0 = (g * kWave + lane) * G;
       const bool valid = FULL || col0 < M;
-      const V v = load_streaming<G>(row + (valid ? col0 : 0));
-      if constexpr (G == 1) {
-        x[rr][g] = v;
-      } else if constexpr (G == 2) {
-        x[rr][g * 2 + 0] = v.x;
-        x[rr][g * 2 + 1] = v.y;
-      } else {
-        x[rr][g * 4 + 0] = v.x;
-        x[rr][g * 4 + 1] = v.y;
-        x[rr][g * 4 + 2] = v.z;
-        x[rr][g * 4 + 3] = v.w;
-      }
+      float v[G];
+      load_group<DT, G>(row, valid ? col0 : 0, v);
+#pragma unroll
+      for (int c = 0; c < G; ++c) x[rr][g * G + c] = v[c];
     }
   }
   // Searching and selecting stages, row by row.
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
     if (rr < nrows) {
-      const int it = select_row<G, NG, FULL, MODE, NEG>(x[rr], lane, M, k, max_iter, eps_rel, stage + (size_t)rr * k);
+      const int it =
+          select_row<G, NG, FULL, MODE, NEG, DT>(x[rr], lane, M, k, max_iter, eps_rel, stage + (size_t)rr * k);
       if constexpr (MODE == kEps) {
         if (out_iters != nullptr && lane == 0) out_iters[r0 + rr] = it;
       }
@@ -559,14 +618,21 @@ __global__ void __launch_bounds__(256)
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   const int total = nrows * k;
-  float* ov = out_vals + r0 * (int64_t)k;
+  using OutT = typename std::conditional<DT == kF32, uint32_t, uint16_t>::type;  // value bits as stored
+  OutT* ov = static_cast<OutT*>(out_vals) + r0 * (int64_t)k;
   IdxT* oi = out_idx + r0 * (int64_t)k;
   if (vec_store) {
 #pragma unroll 1
     for (int q = lane; q < (total >> 2); q += kWave) {
       const uint4 a = *reinterpret_cast<const uint4*>(stage + 4 * q);
       const uint4 b = *reinterpret_cast<const uint4*>(stage + 4 * q + 2);
-      store_streaming(reinterpret_cast<uint4*>(ov) + q, make_uint4(a.x, a.z, b.x, b.z));
+      if constexpr (DT == kF32) {
+        store_streaming(reinterpret_cast<uint4*>(ov) + q, make_uint4(a.x, a.z, b.x, b.z));
+      } else {
+        store_streaming(reinterpret_cast<uint2*>(ov) + q,
+                        make_uint2(narrow_bits<DT>(a.x) | (narrow_bits<DT>(a.z) << 16),
+                                   narrow_bits<DT>(b.x) | (narrow_bits<DT>(b.z) << 16)));
+      }
       if constexpr (sizeof(IdxT) == 4) {
         store_streaming(reinterpret_cast<uint4*>(oi) + q, make_uint4(a.y, a.w, b.y, b.w));
       } else {
@@ -577,7 +643,11 @@ __global__ void __launch_bounds__(256)
 #pragma unroll 1
     for (int q = lane; q < total; q += kWave) {
       const uint2 a = stage[q];
-      ov[q] = __uint_as_float(a.x);
+      if constexpr (DT == kF32) {
+        ov[q] = a.x;
+      } else {
+        ov[q] = (uint16_t)narrow_bits<DT>(a.x);
+      }
       oi[q] = (IdxT)a.y;
     }
   }
@@ -585,7 +655,7 @@ __global__ void __launch_bounds__(256)
 
 // ---- host-side launcher -------------------------------------------------------------------------------
 
-template <int G, int NG, int R, bool FULL, int MODE, typename IdxT, bool NEG = false>
+template <int G, int NG, int R, bool FULL, int MODE, typename IdxT, bool NEG = false, int DT = kF32>
 hipError_t launch(const LaunchArgs& a) {
   // LDS per wavefront: R*k staged pairs of 8 bytes; at most 64 KiB per block.
   const size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
@@ -594,7 +664,7 @@ hipError_t launch(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((rtopk_wave_kernel<G, NG, R, FULL, MODE, NEG, IdxT>), dim3((unsigned)blocks), dim3(waves * kWave),
+  hipLaunchKernelGGL((rtopk_wave_kernel<G, NG, R, FULL, MODE, NEG, IdxT, DT>), dim3((unsigned)blocks), dim3(waves * kWave),
                      per_wave * waves, a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
                      static_cast<IdxT*>(a.out_idx), a.out_iters, a.vec_store);
   return hipGetLastError();

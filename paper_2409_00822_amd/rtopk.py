@@ -36,6 +36,12 @@ def load_library() -> ctypes.CDLL:
         lib.rtopk_rowwise_exact.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_exact_u8.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.rtopk_rowwise_eps.argtypes = [vp, i64, i32, i32, ctypes.c_float, vp, vp, vp, vp]
+        for name in ("rtopk_rowwise_f16", "rtopk_rowwise_bf16"):
+            getattr(lib, name).argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+            getattr(lib, name).restype = ctypes.c_int
+        for name in ("rtopk_rowwise_exact_f16", "rtopk_rowwise_exact_bf16"):
+            getattr(lib, name).argtypes = [vp, i64, i32, i32, vp, vp, vp]
+            getattr(lib, name).restype = ctypes.c_int
         for fn in (lib.rtopk_rowwise, lib.rtopk_rowwise_u8, lib.rtopk_rowwise_exact, lib.rtopk_rowwise_exact_u8,
                    lib.rtopk_rowwise_eps, lib.rtopk_rowwise_smallest, lib.rtopk_rowwise_exact_smallest,
                    lib.rtopk_version, lib.rtopk_max_m):
@@ -63,17 +69,18 @@ def _check(status: int) -> None:
         raise RTopKError(status, rtopk_status_string(status))
 
 
-def _prepare(x, k: int, out_vals, out_idx, idx_dtype):
+def _prepare(x, k: int, out_vals, out_idx, idx_dtype, val_dtype=None):
     import torch
 
-    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.is_contiguous()):
-        raise ValueError("x must be a contiguous 2-D float32 tensor on the GPU")
+    val_dtype = torch.float32 if val_dtype is None else val_dtype
+    if not (x.is_cuda and x.dtype == val_dtype and x.dim() == 2 and x.is_contiguous()):
+        raise ValueError(f"x must be a contiguous 2-D {val_dtype} tensor on the GPU")
     N, M = x.shape
     if out_vals is None:
-        out_vals = torch.empty((N, k), dtype=torch.float32, device=x.device)
+        out_vals = torch.empty((N, k), dtype=val_dtype, device=x.device)
     if out_idx is None:
         out_idx = torch.empty((N, k), dtype=idx_dtype, device=x.device)
-    for t, dt in ((out_vals, torch.float32), (out_idx, idx_dtype)):
+    for t, dt in ((out_vals, val_dtype), (out_idx, idx_dtype)):
         if not (t.is_cuda and t.dtype == dt and t.is_contiguous() and tuple(t.shape) == (N, k)):
             raise ValueError("outputs must be contiguous [N, k] GPU tensors of the right dtype")
     stream = torch.cuda.current_stream(x.device).cuda_stream
@@ -154,3 +161,43 @@ def rtopk_rowwise_exact_smallest(x, k: int, out_vals=None, out_idx=None):
     _check(load_library().rtopk_rowwise_exact_smallest(x.data_ptr(), N, M, k, out_vals.data_ptr(), out_idx.data_ptr(),
                                                        stream))
     return out_vals, out_idx
+
+
+def _rowwise_16(name: str, val_dtype, x, k, max_iter, out_vals, out_idx):
+    import torch
+
+    N, M, out_vals, out_idx, stream = _prepare(x, k, out_vals, out_idx, torch.int32, val_dtype)
+    fn = getattr(load_library(), name)
+    if max_iter is None:
+        _check(fn(x.data_ptr(), N, M, k, out_vals.data_ptr(), out_idx.data_ptr(), stream))
+    else:
+        _check(fn(x.data_ptr(), N, M, k, max_iter, out_vals.data_ptr(), out_idx.data_ptr(), stream))
+    return out_vals, out_idx
+
+
+def rtopk_rowwise_f16(x, k: int, max_iter: int, out_vals=None, out_idx=None):
+    """Algorithm 2 on float16 rows (fp32 arithmetic on the widened row).  Returns (values f16, columns i32)."""
+    import torch
+
+    return _rowwise_16("rtopk_rowwise_f16", torch.float16, x, k, max_iter, out_vals, out_idx)
+
+
+def rtopk_rowwise_exact_f16(x, k: int, out_vals=None, out_idx=None):
+    """Exact top-k of float16 rows.  Returns (values f16, columns i32)."""
+    import torch
+
+    return _rowwise_16("rtopk_rowwise_exact_f16", torch.float16, x, k, None, out_vals, out_idx)
+
+
+def rtopk_rowwise_bf16(x, k: int, max_iter: int, out_vals=None, out_idx=None):
+    """Algorithm 2 on bfloat16 rows (fp32 arithmetic on the widened row).  Returns (values bf16, columns i32)."""
+    import torch
+
+    return _rowwise_16("rtopk_rowwise_bf16", torch.bfloat16, x, k, max_iter, out_vals, out_idx)
+
+
+def rtopk_rowwise_exact_bf16(x, k: int, out_vals=None, out_idx=None):
+    """Exact top-k of bfloat16 rows.  Returns (values bf16, columns i32)."""
+    import torch
+
+    return _rowwise_16("rtopk_rowwise_exact_bf16", torch.bfloat16, x, k, None, out_vals, out_idx)

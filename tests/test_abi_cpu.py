@@ -29,6 +29,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"rtopk_rowwise", "rtopk_rowwise_exact", "rtopk_rowwise_u8", "rtopk_rowwise_exact_u8", "rtopk_rowwise_eps", "rtopk_rowwise_smallest", "rtopk_rowwise_exact_smallest",
+            "rtopk_rowwise_f16", "rtopk_rowwise_exact_f16", "rtopk_rowwise_bf16", "rtopk_rowwise_exact_bf16",
             "rtopk_status_string", "rtopk_version", "rtopk_max_m"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -75,6 +76,20 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert f(p + 2, 4, 256, 32, 8, p, p, None) == -5
     assert f(p, 4, 256, 32, 8, p + 1, p, None) == -5
     assert f(p, 4, 256, 32, 8, p, p + 2, None) == -5
+    # rows stored in 16 bits: 2-byte alignment is enough for values, the other checks are shared
+    for name in ("rtopk_rowwise_f16", "rtopk_rowwise_bf16"):
+        h = getattr(lib, name)
+        assert h(p + 2, 0, 256, 32, 8, p + 2, p, None) == 0
+        assert h(None, 4, 256, 32, 8, p, p, None) == -1
+        assert h(p + 1, 4, 256, 32, 8, p, p, None) == -5
+        assert h(p, 4, 256, 32, 8, p + 1, p, None) == -5
+        assert h(p, 4, 256, 32, -2, p, p, None) == -3
+        assert h(p, 4, 256, 300, 8, p, p, None) == -2
+        assert h(p, 4, 9000, 32, 8, p, p, None) == -4
+    for name in ("rtopk_rowwise_exact_f16", "rtopk_rowwise_exact_bf16"):
+        h = getattr(lib, name)
+        assert h(p, 4, 9000, 32, p, p, None) == -4
+        assert h(p, 4, 256, 0, p, p, None) == -2
 
 
 def test_binding_refuses_host_tensors():
