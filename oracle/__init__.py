@@ -180,3 +180,17 @@ def topk_earlystop_16(bits16: np.ndarray, kind: str, k: int, max_iter: int):
     """Algorithm 2 in fp32 on the widened row.  Returns (value bits [N,k] u16, idx [N,k] i32)."""
     _, idx = topk_earlystop(widen16(bits16, kind), k, max_iter)
     return _gather16(bits16, idx), idx
+
+
+# ---------------------------------------------------------------------------------------------
+# Dense form of the selection (the MaxK non-linearity, Section 1 / Fig. 1): the selected values in
+# place, +0 everywhere else.  Written out from the column lists the functions above return.
+# ---------------------------------------------------------------------------------------------
+def maxk_dense(x: np.ndarray, k: int, max_iter: int = -1) -> np.ndarray:
+    """max_iter < 0: exact top-k; otherwise Algorithm 2 with max_iter steps.  Returns [N, M] fp32."""
+    x = _check_in(x)
+    _, idx = topk_exact(x, k) if max_iter < 0 else topk_earlystop(x, k, max_iter)
+    out = np.zeros_like(x)
+    rows = np.arange(x.shape[0])[:, None]
+    out[rows, idx] = x[rows, idx]
+    return out

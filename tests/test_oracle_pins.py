@@ -359,3 +359,37 @@ def test_oracle_rejects_bad_arguments():
         oracle.topk_exact(x, 9)
     with pytest.raises(ValueError):
         oracle.topk_earlystop(x, 3, -1)
+
+
+# --------------------------------------------------------------------------------------------
+# dense form (MaxK non-linearity)
+# --------------------------------------------------------------------------------------------
+def test_maxk_dense_equals_thresholding_at_the_kth_value_on_tie_free_rows():
+    x = workloads.normal(500, 96, seed=1200)  # continuous values: no ties
+    for k in (1, 12, 95, 96):
+        d = oracle.maxk_dense(x, k)
+        kth = np.sort(x, axis=1)[:, ::-1][:, k - 1:k]
+        assert np.array_equal(bits(d), bits(np.where(x >= kth, x, np.float32(0.0))))
+        t = torch.from_numpy(x)
+        tv, ti = torch.topk(t, k, dim=1)
+        assert np.array_equal(bits(d), bits(torch.zeros_like(t).scatter_(1, ti, tv).numpy()))
+
+
+def test_maxk_dense_under_ties_keeps_exactly_k_entries_lowest_columns_first():
+    x = workloads.small_ints(300, 20, seed=1201, span=2) + np.float32(10.0)  # all positive, heavy ties
+    for k in (1, 7, 19):
+        d = oracle.maxk_dense(x, k)
+        assert ((d != 0).sum(axis=1) == k).all()
+        for r in range(x.shape[0]):
+            cols = brute_topk(x[r], k)
+            exp = np.zeros(20, dtype=np.float32)
+            exp[cols] = x[r][cols]
+            assert np.array_equal(d[r], exp)
+
+
+def test_maxk_dense_early_stop_follows_alg2_hand_traces():
+    for v, k, mi, exp in _handtrace_cases():
+        d = oracle.maxk_dense(v[None, :], k, mi)[0]
+        ref = np.zeros_like(v)
+        ref[exp] = v[exp]
+        assert np.array_equal(bits(d), bits(ref))
