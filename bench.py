@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--rows", type=int, default=None, help="override the workload's N")
     ap.add_argument("--k", type=int, default=None, help="default: 32 for M=256, else the workload's first k")
     ap.add_argument("--max-iter", type=int, default=8)
+    ap.add_argument("--op", default="pairs", choices=("pairs", "dense"),
+                    help="pairs: k (value, column) pairs per row (the headline); dense: the selected values in place "
+                         "and zero elsewhere (rtopk_maxk_dense, fp32 only)")
     ap.add_argument("--dtype", default="f32", choices=("f32", "f16", "bf16"),
                     help="storage type of the rows and of the value output (16-bit types: the same matrix rounded "
                          "to nearest; the search still runs in fp32)")
@@ -139,11 +142,24 @@ def main():
         f_exact = R.rtopk_rowwise_exact_u8 if u8 else R.rtopk_rowwise_exact
         f_early = R.rtopk_rowwise_u8 if u8 else R.rtopk_rowwise
 
+    dense = args.op == "dense"
+    if dense:
+        assert not half, "--op dense is fp32 only"
+        u8 = False
+        out_d = torch.empty_like(x)
+        algo_bytes = N * M * 8  # read the row once, write it once
+
     def exact():
-        f_exact(x, k, out_v, out_i)
+        if dense:
+            R.rtopk_maxk_dense(x, k, -1, out_d)
+        else:
+            f_exact(x, k, out_v, out_i)
 
     def early():
-        f_early(x, k, max_iter, out_v, out_i)
+        if dense:
+            R.rtopk_maxk_dense(x, k, max_iter, out_d)
+        else:
+            f_early(x, k, max_iter, out_v, out_i)
 
     log("timing exact mode ...")
     spin_up(torch, exact, args.spinup_ms)
@@ -169,6 +185,8 @@ def main():
     if not args.no_parity:
         log("parity against the CPU oracle on every row ...")
         def out_bits():
+            if dense:
+                return out_d.cpu().numpy().view(np.int32)
             if half:
                 return out_v.view(torch.int16).cpu().numpy().view(np.uint16)
             return out_v.cpu().numpy().view(np.int32)
@@ -182,11 +200,18 @@ def main():
             ev, sv = ev.view(np.int32), sv.view(np.int32)
         exact()
         torch.cuda.synchronize()
-        ok_e = bool(np.array_equal(out_i.cpu().numpy().astype(np.int32), ei) and np.array_equal(out_bits(), ev))
+        if dense:
+            ok_e = bool(np.array_equal(out_bits(), oracle.maxk_dense(x_host, k).view(np.int32)))
+        else:
+            ok_e = bool(np.array_equal(out_i.cpu().numpy().astype(np.int32), ei) and np.array_equal(out_bits(), ev))
         early()
         torch.cuda.synchronize()
-        gi = out_i.cpu().numpy().astype(np.int32)
-        ok_s = bool(np.array_equal(gi, si) and np.array_equal(out_bits(), sv))
+        if dense:
+            ok_s = bool(np.array_equal(out_bits(), oracle.maxk_dense(x_host, k, max_iter).view(np.int32)))
+            gi = si
+        else:
+            gi = out_i.cpu().numpy().astype(np.int32)
+            ok_s = bool(np.array_equal(gi, si) and np.array_equal(out_bits(), sv))
         parity = {"exact": ok_e, "early_stop": ok_s}
         recall = oracle.mean_overlap(gi, ei)
         log(f"  parity {parity}, early-stop recall vs exact {recall:.4f}")
@@ -221,16 +246,16 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "%s: N=%d x M=%d %s, %s, seed %d" % (args.workload, N, M, args.dtype, cfg["dist"], cfg["seed"]),
-                   "k": k, "mode": "exact", "index_type": "uint8" if u8 else "int32"},
+                   "k": k, "mode": "exact", "index_type": "uint8" if u8 else "int32", "output": args.op},
         "early_stop": {"max_iter": max_iter, "rows_per_s": N * args.steps / wall_s,
                        "ms_per_step": wall_s / args.steps * 1e3,
                        "hbm_gbps": algo_bytes / launch_s / 1e9, "recall_vs_exact": recall},
         "parity_vs_oracle": parity,
         "roofline": {"bound": "hbm", "achieved": algo_bytes / launch_e / 1e9, "peak": PEAK_HBM_GBPS,
                      "unit": "GB/s", "frac": algo_bytes / launch_e / 1e9 / PEAK_HBM_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES if (args.workload, N, k, args.dtype) == ("c1_maxk", 1 << 20, 32, "f32") else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES if (args.workload, N, k, args.dtype, args.op) == ("c1_maxk", 1 << 20, 32, "f32", "pairs") else None,
                      "traffic_source": "profiles/rtopk_wave_kernel_c1_maxk_pmc.md (FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
-                     "kernel": "rtopk_wave_kernel, exact mode, M=%d" % M,
+                     "kernel": "%s, exact mode, M=%d" % ("rtopk_dense_kernel" if dense else "rtopk_wave_kernel", M),
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": launch_e * 1e6},
         "cpu_baseline": cpu,
     }

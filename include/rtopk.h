@@ -118,6 +118,17 @@ int rtopk_rowwise_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k, int3
 int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k, uint16_t* out_vals,
                              int32_t* out_idx, void* stream);
 
+/*
+ * The MaxK non-linearity in dense form (Section 1 and Fig. 1: MaxK-GNN applies row-wise top-k to the
+ * feature matrix before aggregation; Section 4.3 measures it inside MaxK-GNN training):
+ *   out[r][c] = in[r][c] if column c is one of the k columns selected for row r, +0.0f otherwise.
+ * The selected columns are exactly those of rtopk_rowwise_exact (max_iter < 0) or of
+ * rtopk_rowwise with that max_iter (max_iter >= 0).  `in` and `out` are [N][M] fp32, dense,
+ * row-major, 4-byte aligned (fastest when both are 16-byte aligned and M is a multiple of 4), and must
+ * not overlap.  One launch; the row is read once and written once, nothing else touches memory.
+ */
+int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out, void* stream);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* rtopk_status_string(int status);
 

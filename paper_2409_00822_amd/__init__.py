@@ -10,6 +10,7 @@ from .rtopk import (  # noqa: F401
     lib_path,
     load_library,
     rtopk_max_m,
+    rtopk_maxk_dense,
     rtopk_rowwise,
     rtopk_rowwise_bf16,
     rtopk_rowwise_exact_bf16,

@@ -161,6 +161,45 @@ int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k
   return run(in, N, M, k, 0, 0.0f, rtopk::kExact, out_vals, out_idx, nullptr, false, stream, false, rtopk::kBF16);
 }
 
+int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out, void* stream) {
+  if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
+  if (M > kMaxM) return RTOPK_ERR_M_TOO_LARGE;
+  if (N == 0) return RTOPK_OK;
+  if (!in || !out) return RTOPK_ERR_NULL_POINTER;
+  if (!aligned(in, 4) || !aligned(out, 4)) return RTOPK_ERR_MISALIGNED;
+  int mode = max_iter < 0 ? rtopk::kExact : rtopk::kEarly;
+  if (mode == rtopk::kExact && k == M) {  // everything is kept: no search needed
+    mode = rtopk::kEarly;
+    max_iter = 0;
+  }
+  rtopk::LaunchArgs a{};
+  a.in = in;
+  a.N = N;
+  a.M = M;
+  a.k = k;
+  a.max_iter = max_iter < 0 ? 0 : max_iter;
+  a.out_vals = out;
+  a.stream = static_cast<hipStream_t>(stream);
+  int g = 1, ng = 1;
+  if (M > 128 && M % 4 == 0 && aligned(in, 16) && aligned(out, 16)) {
+    static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+    g = 4;
+    ng = 32;
+    for (int cand : kNg) {
+      if (M <= 256 * cand) {
+        ng = cand;
+        break;
+      }
+    }
+  } else if (M > 64 && M <= 128 && M % 2 == 0 && aligned(in, 8) && aligned(out, 8)) {
+    g = 2;
+  } else {
+    while (64 * ng < M) ng <<= 1;
+  }
+  const hipError_t err = rtopk::launch_dense_any(g, ng, M == 64 * g * ng, mode, a);
+  return err == hipSuccess ? RTOPK_OK : RTOPK_ERR_LAUNCH;
+}
+
 const char* rtopk_status_string(int status) {
   switch (status) {
     case RTOPK_OK: return "ok";

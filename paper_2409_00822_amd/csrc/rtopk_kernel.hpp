@@ -294,6 +294,68 @@ __device__ __forceinline__ int nth_column_in_band(const float (&x)[G * NG], int 
   return __builtin_amdgcn_readlane(v, 63);
 }
 
+// x where bit `lane` of mask is set, +0 elsewhere: one v_cndmask with the lane mask as its condition.
+__device__ __forceinline__ float keep_where(float x, uint64_t mask) {
+  float r;
+  asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(x), "s"(mask));
+  return r;
+}
+
+// Selecting stage in dense form (the MaxK non-linearity as MaxK-GNN applies it before aggregation,
+// Section 1 / Fig. 1): y[e] = x[e] for the chosen elements and +0 for all others, in the row's own
+// register layout, so that the result goes back to memory with the same coalesced accesses the row
+// came in with.  Same candidates, order and cut as compact_masks.
+template <int G, int NG, bool CUT, bool LAZY, bool NEG>
+__device__ __forceinline__ void mask_dense(const float (&x)[G * NG], const uint64_t* mm, float t_hi, float t_lo,
+                                           int split_col, int lane, int limit, float (&y)[G * NG]) {
+  uint32_t base = 0;  // wave-uniform: candidates in earlier groups
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    int ln = lane;  // opaque per group, see compact_masks
+    if constexpr (NG > 4) asm volatile("" : "+v"(ln));
+    uint64_t m[G];
+#pragma unroll
+    for (int c = 0; c < G; ++c) {
+      if constexpr (LAZY) {
+        const int col = (g * kWave + ln) * G + c;
+        m[c] = __builtin_amdgcn_ballot_w64(keyof<NEG>(x[g * G + c]) >= (col <= split_col ? t_lo : t_hi));
+      } else {
+        m[c] = mm[g * G + c];
+      }
+    }
+    if constexpr (CUT) {
+      uint32_t pos = base;
+#pragma unroll
+      for (int c = 0; c < G; ++c) pos = lanes_below(m[c], pos);
+#pragma unroll
+      for (int c = 0; c < G; ++c) {
+        y[g * G + c] = keep_where(x[g * G + c], m[c] & __builtin_amdgcn_ballot_w64(pos < (uint32_t)limit));
+        if (c + 1 < G) pos = add_mask_bit(pos, m[c]);
+      }
+      if (g + 1 < NG) {
+#pragma unroll
+        for (int c = 0; c < G; ++c) base += (uint32_t)__builtin_popcountll(m[c]);
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < G; ++c) y[g * G + c] = keep_where(x[g * G + c], m[c]);
+    }
+    if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// The selection in the form the kernel wants: (value, column) pairs staged in LDS, or the dense row.
+template <int G, int NG, bool CUT, bool LAZY, bool NEG, bool DENSE>
+__device__ __forceinline__ void emit_selection(const float (&x)[G * NG], const uint64_t* mm, float t_hi, float t_lo,
+                                               int split_col, int lane, int limit, uint32_t stage_addr,
+                                               float (&y)[G * NG]) {
+  if constexpr (DENSE) {
+    mask_dense<G, NG, CUT, LAZY, NEG>(x, mm, t_hi, t_lo, split_col, lane, limit, y);
+  } else {
+    compact_masks<G, NG, CUT, LAZY, NEG>(x, mm, t_hi, t_lo, split_col, lane, limit, stage_addr);
+  }
+}
+
 // Hand-scheduled search loops for 2, 4 and 8 values per lane: search_exact_asm / search_early_asm
 // (generated by gen_search_loops.py; same steps as the generic loops in select_row).
 #include "rtopk_search_loops.inc"
@@ -316,9 +378,10 @@ __device__ __forceinline__ float midpoint_exact(float lo, float hi) {
   }
 }
 
-template <int G, int NG, bool FULL, int MODE, bool NEG, int DT = kF32>
+//   DENSE: the result is y[] (chosen values in place, +0 elsewhere) instead of pairs staged at `stage`.
+template <int G, int NG, bool FULL, int MODE, bool NEG, int DT = kF32, bool DENSE = false>
 __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, int M, int k, int max_iter,
-                                          float eps_rel, uint2* stage) {
+                                          float eps_rel, uint2* stage, float (&y)[G * NG]) {
   constexpr int E = G * NG;
   const uint32_t stage_addr = (uint32_t)(uintptr_t)stage;  // LDS byte address
 
@@ -409,14 +472,14 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       }
     }
     if (hit) {
-      compact_masks<G, NG, false, !KEEP, NEG>(x, m, thres, thres, -1, lane, k, stage_addr);
+      emit_selection<G, NG, false, !KEEP, NEG, DENSE>(x, m, thres, thres, -1, lane, k, stage_addr, y);
     } else {
       // Everything >= hi is taken first (cut at k by column when hi is still the row maximum and k
       // or more tie there); the first k - na members of [lo, hi) follow: all columns up to the
       // (k - na)-th member's column select against lo, the others against hi.
       const int na = count(hi);
       const int split = nth_column_in_band<G, NG, NEG>(x, lane, hi, lo, k - (na < k ? na : k));
-      compact_masks<G, NG, true, true, NEG>(x, nullptr, hi, lo, split, lane, k, stage_addr);
+      emit_selection<G, NG, true, true, NEG, DENSE>(x, nullptr, hi, lo, split, lane, k, stage_addr, y);
     }
     return 0;
   } else if constexpr (MODE == kEps) {
@@ -440,12 +503,12 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       move_bound(lo, hi, thres, cnt, k);
     }
     if (hit) {
-      compact_masks<G, NG, false, !KEEP, NEG>(x, m, thres, thres, -1, lane, k, stage_addr);
+      emit_selection<G, NG, false, !KEEP, NEG, DENSE>(x, m, thres, thres, -1, lane, k, stage_addr, y);
       return steps;
     }
     const int na = count(hi);
     const int split = nth_column_in_band<G, NG, NEG>(x, lane, hi, lo, k - (na < k ? na : k));
-    compact_masks<G, NG, true, true, NEG>(x, nullptr, hi, lo, split, lane, k, stage_addr);
+    emit_selection<G, NG, true, true, NEG, DENSE>(x, nullptr, hi, lo, split, lane, k, stage_addr, y);
     return steps + 1;
   } else {
     int cnt = -1;
@@ -463,9 +526,9 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     }
     if (cnt < k) cnt = count(lo);  // the last step lowered hi (or none ran): the masks are not for lo
     if (cnt == k) {
-      compact_masks<G, NG, false, !KEEP, NEG>(x, m, lo, lo, -1, lane, k, stage_addr);
+      emit_selection<G, NG, false, !KEEP, NEG, DENSE>(x, m, lo, lo, -1, lane, k, stage_addr, y);
     } else {
-      compact_masks<G, NG, true, !KEEP, NEG>(x, m, lo, lo, -1, lane, k, stage_addr);
+      emit_selection<G, NG, true, !KEEP, NEG, DENSE>(x, m, lo, lo, -1, lane, k, stage_addr, y);
     }
     return 0;
   }
@@ -555,7 +618,10 @@ __device__ __forceinline__ void load_group(const typename std::conditional<DT ==
 __device__ __forceinline__ void store_streaming(uint4* p, uint4 v) {
   typedef uint32_t u4 __attribute__((ext_vector_type(4)));
   const u4 d = {v.x, v.y, v.z, v.w};
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
+  // A store of more than 64 bits reads its data registers late: a vector instruction that overwrites
+  // them within the next two issue slots would corrupt the stored value.  The compiler pads its own
+  // stores for this but cannot see inside an asm block, so the padding is written out here.
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(d) : "memory");
 }
 __device__ __forceinline__ void store_streaming(uint2* p, uint2 v) {
   typedef uint32_t u2 __attribute__((ext_vector_type(2)));
@@ -605,8 +671,9 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
     if (rr < nrows) {
-      const int it =
-          select_row<G, NG, FULL, MODE, NEG, DT>(x[rr], lane, M, k, max_iter, eps_rel, stage + (size_t)rr * k);
+      float unused[E];
+      const int it = select_row<G, NG, FULL, MODE, NEG, DT, false>(x[rr], lane, M, k, max_iter, eps_rel,
+                                                                    stage + (size_t)rr * k, unused);
       if constexpr (MODE == kEps) {
         if (out_iters != nullptr && lane == 0) out_iters[r0 + rr] = it;
       }
@@ -651,6 +718,77 @@ __global__ void __launch_bounds__(256)
       oi[q] = (IdxT)a.y;
     }
   }
+}
+
+// ---- dense-output kernel -------------------------------------------------------------------------------
+
+// 128-bit / 64-bit / 32-bit store of G consecutive row elements.
+template <int G>
+__device__ __forceinline__ void store_group(float* p, const float* v) {
+  if constexpr (G == 4) {
+    store_streaming(reinterpret_cast<uint4*>(p),
+                    make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+  } else if constexpr (G == 2) {
+    store_streaming(reinterpret_cast<uint2*>(p), make_uint2(__float_as_uint(v[0]), __float_as_uint(v[1])));
+  } else {
+    store_streaming(reinterpret_cast<uint32_t*>(p), __float_as_uint(v[0]));
+  }
+}
+
+// MaxK non-linearity, dense form: out[r][c] = in[r][c] where column c is among the k selected for
+// row r (Algorithm 1 at epsilon = 0, or Algorithm 2), +0 elsewhere.  Same loading, min/max and
+// search as rtopk_wave_kernel; the selection is a register-to-register mask, so nothing passes
+// through LDS and each row leaves in the layout it arrived in.
+template <int G, int NG, int R, bool FULL, int MODE>
+__global__ void __launch_bounds__(256)
+    rtopk_dense_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter, float* __restrict__ out) {
+  constexpr int E = G * NG;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int waves_per_block = (int)(blockDim.x >> 6);
+  const int64_t r0 = ((int64_t)blockIdx.x * waves_per_block + wave) * R;
+  if (r0 >= N) return;
+  const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
+
+  float x[R][E];
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    const float* row = in + (r0 + (rr < nrows ? rr : 0)) * (int64_t)M;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const int col0 = (g * kWave + lane) * G;  // lanes past M: see rtopk_wave_kernel
+      const bool valid = FULL || col0 < M;
+      float v[G];
+      load_group<kF32, G>(row, valid ? col0 : 0, v);
+#pragma unroll
+      for (int c = 0; c < G; ++c) x[rr][g * G + c] = v[c];
+    }
+  }
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    if (rr < nrows) {
+      float y[E];
+      select_row<G, NG, FULL, MODE, false, kF32, true>(x[rr], lane, M, k, max_iter, 0.0f, nullptr, y);
+      float* orow = out + (r0 + rr) * (int64_t)M;
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const int col0 = (g * kWave + lane) * G;
+        if (FULL || col0 < M) store_group<G>(orow + col0, &y[g * G]);
+      }
+    }
+  }
+}
+
+template <int G, int NG, int R, bool FULL, int MODE>
+hipError_t launch_dense(const LaunchArgs& a) {
+  const int waves = 4;
+  const int64_t batches = (a.N + R - 1) / R;
+  const int64_t blocks = (batches + waves - 1) / waves;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+  hipLaunchKernelGGL((rtopk_dense_kernel<G, NG, R, FULL, MODE>), dim3((unsigned)blocks), dim3(waves * kWave), 0,
+                     a.stream, static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter,
+                     static_cast<float*>(a.out_vals));
+  return hipGetLastError();
 }
 
 // ---- host-side launcher -------------------------------------------------------------------------------

@@ -42,6 +42,8 @@ def load_library() -> ctypes.CDLL:
         for name in ("rtopk_rowwise_exact_f16", "rtopk_rowwise_exact_bf16"):
             getattr(lib, name).argtypes = [vp, i64, i32, i32, vp, vp, vp]
             getattr(lib, name).restype = ctypes.c_int
+        lib.rtopk_maxk_dense.argtypes = [vp, i64, i32, i32, i32, vp, vp]
+        lib.rtopk_maxk_dense.restype = ctypes.c_int
         for fn in (lib.rtopk_rowwise, lib.rtopk_rowwise_u8, lib.rtopk_rowwise_exact, lib.rtopk_rowwise_exact_u8,
                    lib.rtopk_rowwise_eps, lib.rtopk_rowwise_smallest, lib.rtopk_rowwise_exact_smallest,
                    lib.rtopk_version, lib.rtopk_max_m):
@@ -201,3 +203,20 @@ def rtopk_rowwise_exact_bf16(x, k: int, out_vals=None, out_idx=None):
     import torch
 
     return _rowwise_16("rtopk_rowwise_exact_bf16", torch.bfloat16, x, k, None, out_vals, out_idx)
+
+
+def rtopk_maxk_dense(x, k: int, max_iter: int = -1, out=None):
+    """MaxK non-linearity, dense form: the k selected values of each row in place, zero elsewhere.
+    max_iter < 0: exact selection; max_iter >= 0: Algorithm 2 with that many steps.  Returns out [N,M] f32."""
+    import torch
+
+    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.is_contiguous()):
+        raise ValueError("x must be a contiguous 2-D float32 tensor on the GPU")
+    N, M = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    if not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (N, M)):
+        raise ValueError("out must be a contiguous [N, M] float32 GPU tensor")
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(load_library().rtopk_maxk_dense(x.data_ptr(), N, M, k, max_iter, out.data_ptr(), stream))
+    return out

@@ -29,7 +29,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"rtopk_rowwise", "rtopk_rowwise_exact", "rtopk_rowwise_u8", "rtopk_rowwise_exact_u8", "rtopk_rowwise_eps", "rtopk_rowwise_smallest", "rtopk_rowwise_exact_smallest",
-            "rtopk_rowwise_f16", "rtopk_rowwise_exact_f16", "rtopk_rowwise_bf16", "rtopk_rowwise_exact_bf16",
+            "rtopk_rowwise_f16", "rtopk_rowwise_exact_f16", "rtopk_rowwise_bf16", "rtopk_rowwise_exact_bf16", "rtopk_maxk_dense",
             "rtopk_status_string", "rtopk_version", "rtopk_max_m"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -76,6 +76,14 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert f(p + 2, 4, 256, 32, 8, p, p, None) == -5
     assert f(p, 4, 256, 32, 8, p + 1, p, None) == -5
     assert f(p, 4, 256, 32, 8, p, p + 2, None) == -5
+    fd = lib.rtopk_maxk_dense
+    assert fd(p, 0, 256, 32, -1, p, None) == 0
+    assert fd(None, 4, 256, 32, -1, p, None) == -1
+    assert fd(p, 4, 256, 32, 8, None, None) == -1
+    assert fd(p, 4, 256, 300, 8, p, None) == -2
+    assert fd(p, 4, 9000, 32, 8, p, None) == -4
+    assert fd(p + 2, 4, 256, 32, 8, p, None) == -5
+    assert fd(p, 4, 256, 32, 8, p + 3, None) == -5
     # rows stored in 16 bits: 2-byte alignment is enough for values, the other checks are shared
     for name in ("rtopk_rowwise_f16", "rtopk_rowwise_bf16"):
         h = getattr(lib, name)

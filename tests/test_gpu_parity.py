@@ -400,3 +400,62 @@ def test_config3_ties_uint8_full_size():
 def test_config4_wide_rows_full_size():
     _full("c4_wide", 64, "exact")
     _full("c4_wide", 256, "exact")
+
+
+# ----------------------------------------------------------------------------------------------
+# dense form (MaxK non-linearity): selected values in place, zero elsewhere
+# ----------------------------------------------------------------------------------------------
+def assert_dense_parity(R, x_np, k, max_iter, tag="", x_dev=None):
+    xd = torch.from_numpy(x_np).cuda() if x_dev is None else x_dev
+    g = R.rtopk_maxk_dense(xd, k, max_iter)
+    torch.cuda.synchronize()
+    o = oracle.maxk_dense(x_np, k, max_iter)
+    g = g.cpu().numpy()
+    if not np.array_equal(bits(g), bits(o)):
+        bad = np.nonzero((bits(g) != bits(o)).any(axis=1))[0]
+        r = int(bad[0])
+        raise AssertionError(f"{tag} dense rows differ in {bad.size} rows; first row {r}: "
+                             f"gpu cols {np.nonzero(g[r])[0]} oracle cols {np.nonzero(o[r])[0]}")
+
+
+@pytest.mark.parametrize("N,M,ks", SHAPES)
+def test_dense_small_shapes(N, M, ks):
+    R = _gpu()
+    x = workloads.normal(N, M, seed=N * 13 + M)
+    xd = torch.from_numpy(x).cuda()
+    for k in ks:
+        for mi in (-1, 0, 3, 8, 40):
+            assert_dense_parity(R, x, k, mi, tag=f"dense N={N} M={M} k={k} max_iter={mi}", x_dev=xd)
+
+
+@pytest.mark.parametrize("M", [8, 64, 128, 256, 1024, 4096])
+def test_dense_tie_heavy_rows(M):
+    R = _gpu()
+    for x in (workloads.from_pool(300, M, 75 + M), workloads.small_ints(300, M, 76 + M, span=4)):
+        for k in sorted({1, max(1, M // 8), M // 2, M - 1, M}):
+            for mi in (-1, 0, 5, 30):
+                assert_dense_parity(R, x, k, mi, tag=f"dense ties M={M} k={k} mi={mi}")
+
+
+def test_dense_unaligned_pointers_and_guard_bands():
+    R = _gpu()
+    N, M, k = 300, 256, 32
+    x = workloads.normal(N, M, seed=86)
+    pad = 1024
+    ibuf = torch.empty(N * M + 1, dtype=torch.float32, device="cuda")
+    xd = ibuf[1:].view(N, M)
+    xd.copy_(torch.from_numpy(x))
+    obuf = torch.full((N * M + 2 * pad + 1,), 777.0, dtype=torch.float32, device="cuda")
+    od = obuf[pad + 1:pad + 1 + N * M].view(N, M)
+    R.rtopk_maxk_dense(xd, k, -1, od)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(od.cpu().numpy()), bits(oracle.maxk_dense(x, k)))
+    assert (obuf[:pad + 1] == 777.0).all() and (obuf[pad + 1 + N * M:] == 777.0).all()
+
+
+def test_dense_headline_shape_full_size():
+    R = _gpu()
+    x = workloads.make("c1_maxk")
+    xd = torch.from_numpy(x).cuda()
+    assert_dense_parity(R, x, 32, -1, tag="c1 dense exact", x_dev=xd)
+    assert_dense_parity(R, x, 32, 8, tag="c1 dense early", x_dev=xd)
