@@ -13,7 +13,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "librtopk.so")
 
 SOURCES = ["rtopk_api.hip", "rtopk_inst_g4_exact.hip", "rtopk_inst_g4_early.hip", "rtopk_inst_g4_eps.hip",
-           "rtopk_inst_small.hip", "rtopk_inst_h16_exact.hip", "rtopk_inst_h16_early.hip", "rtopk_inst_dense.hip"]
+           "rtopk_inst_small.hip", "rtopk_inst_h16_exact.hip", "rtopk_inst_h16_early.hip", "rtopk_inst_dense.hip", "rtopk_inst_block.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

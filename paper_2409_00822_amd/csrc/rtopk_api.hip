@@ -9,7 +9,8 @@
 
 namespace {
 
-constexpr int kMaxM = 8192;
+constexpr int kMaxM = 65536;     // rtopk_rowwise / rtopk_rowwise_exact (one workgroup per row beyond kMaxWaveM)
+constexpr int kMaxWaveM = 8192;  // widest row one wavefront holds in registers; the limit of every other entry point
 constexpr int kVersion = 400;  // 0.4.0
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -25,7 +26,8 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
   if (mode == rtopk::kEarly && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
   if (mode == rtopk::kEps && !(eps_rel >= 0.0f)) return RTOPK_ERR_BAD_EPSILON;
-  if (M > kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
+  const bool plain = dtype == rtopk::kF32 && !u8 && !smallest && mode != rtopk::kEps;
+  if (M > (plain ? kMaxM : kMaxWaveM) || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
   if (N == 0) return RTOPK_OK;
   if (!in || !out_vals || !out_idx) return RTOPK_ERR_NULL_POINTER;
   if (!aligned(in, esz) || !aligned(out_vals, esz) || (!u8 && !aligned(out_idx, 4)) || !aligned(out_iters, 4))
@@ -53,7 +55,23 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   a.stream = static_cast<hipStream_t>(stream);
 
   hipError_t err;
-  if (dtype != rtopk::kF32) {
+  if (M > kMaxWaveM) {
+    if (N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row: the grid holds 2^31 - 1 rows
+    int g = 1, ng = 16;
+    if (M % 4 == 0 && aligned(in, 16)) {
+      static const int kNg[] = {3, 4, 6, 8, 12, 16};
+      g = 4;
+      for (int cand : kNg) {
+        if (M <= 4096 * cand) {
+          ng = cand;
+          break;
+        }
+      }
+    } else {
+      while (1024 * ng < M) ng <<= 1;
+    }
+    err = rtopk::launch_block_any(g, ng, mode, a);
+  } else if (dtype != rtopk::kF32) {
     // 16-bit rows: the widest load whose 64 lanes the row still fills, else the scalar-load fallback
     int g = 1, ng = 1;
     bool full = false;
@@ -163,7 +181,7 @@ int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k
 
 int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out, void* stream) {
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
-  if (M > kMaxM) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > kMaxWaveM) return RTOPK_ERR_M_TOO_LARGE;
   if (N == 0) return RTOPK_OK;
   if (!in || !out) return RTOPK_ERR_NULL_POINTER;
   if (!aligned(in, 4) || !aligned(out, 4)) return RTOPK_ERR_MISALIGNED;
@@ -206,7 +224,7 @@ const char* rtopk_status_string(int status) {
     case RTOPK_ERR_NULL_POINTER: return "null data pointer with N > 0";
     case RTOPK_ERR_BAD_SHAPE: return "bad shape: need N >= 0 and 1 <= k <= M";
     case RTOPK_ERR_BAD_MAX_ITER: return "max_iter must be >= 0";
-    case RTOPK_ERR_M_TOO_LARGE: return "M exceeds the supported row width (8192; 256 for uint8 columns)";
+    case RTOPK_ERR_M_TOO_LARGE: return "M exceeds the supported row width (65536 for fp32 rows with int32 columns, 8192 otherwise, 256 for uint8 columns)";
     case RTOPK_ERR_MISALIGNED: return "pointer not aligned to its element size";
     case RTOPK_ERR_LAUNCH: return "the HIP runtime refused the launch";
     case RTOPK_ERR_BAD_EPSILON: return "eps_rel must be >= 0";

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_limits_and_status_strings(lib):
     assert lib.rtopk_version() >= 100
-    assert lib.rtopk_max_m() == 8192
+    assert lib.rtopk_max_m() == 65536
     seen = set()
     for code in range(0, -8, -1):
         s = lib.rtopk_status_string(code)
@@ -61,8 +61,11 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert f(p, 4, 256, 0, 8, p, p, None) == -2
     assert f(p, 4, 256, 257, 8, p, p, None) == -2
     assert f(p, 4, 256, 32, -1, p, p, None) == -3
-    assert f(p, 4, 8200, 32, 8, p, p, None) == -4
-    assert fe(p, 4, 8200, 32, p, p, None) == -4
+    assert f(p, 4, 65537, 32, 8, p, p, None) == -4
+    assert fe(p, 4, 70000, 32, p, p, None) == -4
+    assert f(p, 2 ** 31, 9000, 32, 8, p, p, None) == -2   # one workgroup per row beyond 8192 columns: 2^31 - 1 rows
+    assert lib.rtopk_rowwise_smallest(p, 4, 8200, 32, 8, p, p, None) == -4
+    assert lib.rtopk_rowwise_exact_smallest(p, 4, 8200, 32, p, p, None) == -4
     assert lib.rtopk_rowwise_u8(p, 4, 260, 32, 8, p, p, None) == -4
     assert lib.rtopk_rowwise_exact_u8(p, 4, 260, 32, p, p, None) == -4
     fz = lib.rtopk_rowwise_eps

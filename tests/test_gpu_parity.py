@@ -459,3 +459,47 @@ def test_dense_headline_shape_full_size():
     xd = torch.from_numpy(x).cuda()
     assert_dense_parity(R, x, 32, -1, tag="c1 dense exact", x_dev=xd)
     assert_dense_parity(R, x, 32, 8, tag="c1 dense early", x_dev=xd)
+
+
+# ----------------------------------------------------------------------------------------------
+# rows wider than 8192 columns: one workgroup of 16 wavefronts per row
+# ----------------------------------------------------------------------------------------------
+WIDE = [(6, 8193, (1, 100)), (5, 8196, (64, 4000)), (7, 9000, (33, 512)), (4, 12288, (1, 1536)),
+        (9, 16384, (64, 2048, 16383)), (3, 20000, (500,)), (3, 20001, (77,)), (4, 32768, (1, 4096)),
+        (3, 40001, (999,)), (3, 49152, (6144,)), (5, 65536, (64, 8192, 65535, 65536)), (2, 65535, (31,))]
+
+
+@pytest.mark.parametrize("N,M,ks", WIDE)
+def test_very_wide_rows(N, M, ks):
+    R = _gpu()
+    x = workloads.normal(N, M, seed=N * 4099 + M)
+    for k in ks:
+        assert_parity(R, x, k, "exact", tag=f"wide N={N} M={M} k={k}")
+        for mi in (0, 1, 6, 40):
+            assert_parity(R, x, k, "early", mi, tag=f"wide N={N} M={M} k={k} max_iter={mi}")
+
+
+@pytest.mark.parametrize("M", [8200, 16384, 30000, 65536])
+def test_very_wide_tie_heavy_rows(M):
+    R = _gpu()
+    for x in (workloads.from_pool(12, M, 95 + M), workloads.small_ints(12, M, 96 + M, span=20),
+              workloads.normal_ties(12, M, 97 + M, p=0.5)):
+        for k in (1, 64, 1000, M // 2, M - 1, M):
+            assert_parity(R, x, k, "exact", tag=f"wide ties M={M} k={k}")
+            for mi in (0, 5, 30):
+                assert_parity(R, x, k, "early", mi, tag=f"wide ties M={M} k={k} mi={mi}")
+
+
+def test_very_wide_rows_many_rows_and_unaligned_input():
+    R = _gpu()
+    N, M, k = 3000, 16384, 256
+    x = workloads.laplace(N, M, seed=98)
+    assert_parity(R, x, k, "exact", tag="wide many rows")
+    # 4-byte aligned input takes the scalar-load variant
+    buf = torch.empty(64 * M + 1, dtype=torch.float32, device="cuda")
+    xd = buf[1:].view(64, M)
+    xd.copy_(torch.from_numpy(x[:64]))
+    v, i = R.rtopk_rowwise_exact(xd, k)
+    torch.cuda.synchronize()
+    ev, ei = oracle.topk_exact(x[:64], k)
+    assert np.array_equal(i.cpu().numpy(), ei) and np.array_equal(bits(v.cpu().numpy()), bits(ev))
