@@ -360,6 +360,10 @@ __device__ __forceinline__ void emit_selection(const float (&x)[G * NG], const u
 // (generated by gen_search_loops.py; same steps as the generic loops in select_row).
 #include "rtopk_search_loops.inc"
 
+#ifndef RTOPK_ACC_OF
+#define RTOPK_ACC_OF(E) (((E) - 3) / 3)
+#endif
+
 // Search and selection for one row held as xin[E] (lanes past column M hold duplicates of real
 // elements on entry).
 //   MODE: kExact = Algorithm 1 at epsilon = 0, kEarly = Algorithm 2 with max_iter steps,
@@ -432,7 +436,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
   constexpr bool KEEP = E <= 8;                       // masks of the last step stay in scalar registers
   // wider rows: ACC of the E elements are counted per lane, which balances vector against scalar work
   // (2*ACC + (E-ACC) + ~11 vector against 2*(E-ACC) + ~8 scalar instructions per step)
-  constexpr int ACC = KEEP ? 0 : (E - 3) / 3;
+  constexpr int ACC = KEEP ? 0 : RTOPK_ACC_OF(E);
   uint64_t m[KEEP ? E : 1];
   auto count = [&](float t) -> int {
     if constexpr (KEEP) {
