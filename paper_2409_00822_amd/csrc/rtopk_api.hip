@@ -57,20 +57,16 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   hipError_t err;
   if (M > kMaxWaveM) {
     if (N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row: the grid holds 2^31 - 1 rows
-    int g = 1, ng = 16;
+    int g = 1, ng = 16, w = 16;
     if (M % 4 == 0 && aligned(in, 16)) {
-      static const int kNg[] = {3, 4, 6, 8, 12, 16};
+      // a lane holds up to 64 values: 4 wavefronts up to 16384 columns, 8 up to 32768, 16 beyond
       g = 4;
-      for (int cand : kNg) {
-        if (M <= 4096 * cand) {
-          ng = cand;
-          break;
-        }
-      }
+      w = M <= 16384 ? 4 : (M <= 32768 ? 8 : 16);
+      ng = M <= 64 * w * 4 * 12 ? 12 : 16;
     } else {
       while (1024 * ng < M) ng <<= 1;
     }
-    err = rtopk::launch_block_any(g, ng, mode, a);
+    err = rtopk::launch_block_any(g, ng, w, mode, a);
   } else if (dtype != rtopk::kF32) {
     // 16-bit rows: the widest load whose 64 lanes the row still fills, else the scalar-load fallback
     int g = 1, ng = 1;

@@ -8,7 +8,10 @@
 // Layout.  Wavefront w, lane l owns NG groups of G consecutive columns:
 //   element e = g*G + c  <->  column ((g*W + w)*64 + l)*G + c
 // so every load instruction of a wavefront still covers 64*G*4 contiguous bytes, the W wavefronts of a
-// group step cover W KiB contiguous, and column order is (g, w, lane, c).
+// group step cover W KiB contiguous, and column order is (g, w, lane, c).  W is 4, 8 or 16, chosen so
+// that a lane holds up to 64 values: fewer, fatter wavefronts spread the per-step fixed cost (two
+// cross-lane sums, the LDS round trip, the barrier) over more compares, and narrower workgroups leave
+// room for more rows per compute unit, whose load and search phases then overlap.
 //
 // Every wavefront evaluates the same thresholds on the same totals, so all of them take the same
 // branches and reach the same barriers; the trip count of the search is uniform over the workgroup.
@@ -77,8 +80,9 @@ __global__ void __launch_bounds__(W * kWave)
       a = vmax(a, s_hi[w]);
       b = vmax(b, s_nlo[w]);
     }
-    hi = a;
-    lo = -b;
+    // every lane holds the same two values; saying so lets the search loop branch on scalar conditions
+    hi = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a)));
+    lo = -__int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(b)));
   }
 
   // From here on columns past M must never be counted or chosen.
@@ -191,6 +195,41 @@ __global__ void __launch_bounds__(W * kWave)
   // so the stores are still mostly coalesced).
   float* ov = out_vals + r * (int64_t)k;
   int32_t* oi = out_idx + r * (int64_t)k;
+  if (!has_b) {
+    // One class: rank = cell prefix + chosen elements in lower lanes + own earlier elements; the pair
+    // goes to byte offset 4*rank of both outputs under EXEC = (candidate and rank < limA).  The
+    // kernel's control flow is uniform over the wavefront, so EXEC is all ones here and is restored so.
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      int ln = lane;  // opaque per group: keeps the column numbers of all groups from being hoisted
+      if constexpr (NG > 4) asm volatile("" : "+v"(ln));
+      uint64_t m[G];
+      uint32_t pos = (uint32_t)__builtin_amdgcn_readfirstlane(s_tab[0][g * W + wave]);
+#pragma unroll
+      for (int c = 0; c < G; ++c) {
+        m[c] = __builtin_amdgcn_ballot_w64(x[g * G + c] >= tA);
+        pos = lanes_below(m[c], pos);
+      }
+#pragma unroll
+      for (int c = 0; c < G; ++c) {
+        const uint64_t mk = m[c] & __builtin_amdgcn_ballot_w64(pos < (uint32_t)limA);
+        const uint32_t off = pos * 4u;
+        const int32_t col = ((g * W + wave) * kWave + ln) * G + c;
+        asm volatile(
+            "s_mov_b64 exec, %0\n\t"
+            "global_store_dword %1, %2, %3\n\t"
+            "global_store_dword %1, %4, %5\n\t"
+            "s_mov_b64 exec, -1"
+            :
+            : "s"(mk), "v"(off), "v"(x[g * G + c]), "s"(ov), "v"(col), "s"(oi)
+            : "memory");
+        if (c + 1 < G) pos = add_mask_bit(pos, m[c]);
+      }
+      if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);
+    }
+    return;
+  }
+  // Two classes (a search that converged on a value tied across the k-th place): rare, kept plain.
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     uint32_t posA = (uint32_t)s_tab[0][g * W + wave];
@@ -200,7 +239,7 @@ __global__ void __launch_bounds__(W * kWave)
     for (int c = 0; c < G; ++c) {
       const float v = x[g * G + c];
       a[c] = v >= tA;
-      b[c] = has_b && v >= tB && !a[c];
+      b[c] = v >= tB && !a[c];
       posA = lanes_below(__builtin_amdgcn_ballot_w64(a[c]), posA);
       posB = lanes_below(__builtin_amdgcn_ballot_w64(b[c]), posB);
     }

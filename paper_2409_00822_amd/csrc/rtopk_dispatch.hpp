@@ -43,9 +43,9 @@ hipError_t launch_g4_eps(int ng, bool full, const LaunchArgs& a);  // int32 colu
 // (8, 4, 2 or 1: M % g == 0 and `in` aligned to 2*g bytes), ng = loads per lane (M <= 64*g*ng).
 hipError_t launch_h16_exact(int dtype, int g, int ng, bool full, const LaunchArgs& a);
 hipError_t launch_h16_early(int dtype, int g, int ng, bool full, const LaunchArgs& a);
-// Rows wider than 8192 columns (fp32, int32 columns, kEarly / kExact): one workgroup of 16 wavefronts
-// per row.  g = 4 (M % 4 == 0, `in` 16-byte aligned) or 1; ng = loads per lane (M <= 1024*g*ng).
-hipError_t launch_block_any(int g, int ng, int mode, const LaunchArgs& a);
+// Rows wider than 8192 columns (fp32, int32 columns, kEarly / kExact): one workgroup of w wavefronts
+// per row.  g = 4 (M % 4 == 0, `in` 16-byte aligned) or 1; ng = loads per lane (M <= 64*w*g*ng).
+hipError_t launch_block_any(int g, int ng, int w, int mode, const LaunchArgs& a);
 // Dense-output form (fp32; a.out_vals is the [N][M] output, a.out_idx unused).  g, ng, full as above;
 // mode kEarly or kExact.
 hipError_t launch_dense_any(int g, int ng, bool full, int mode, const LaunchArgs& a);

@@ -1,32 +1,32 @@
-// Instantiations: one workgroup of 16 wavefronts per row, for rows wider than 8192 columns.
+// Instantiations: one workgroup of W wavefronts per row, for rows wider than 8192 columns.
+// 128-bit loads: W = 4 up to 16384 columns, 8 up to 32768, 16 up to 65536, with 12 or 16 loads per lane.
+// Scalar-load fallback (M % 4 != 0 or unaligned input): W = 16 with 16, 32 or 64 loads per lane.
 #include "rtopk_block_kernel.hpp"
 
 namespace rtopk {
 
-template <int G, int NG>
+template <int G, int NG, int W>
 static hipError_t pick(int mode, const LaunchArgs& a) {
-  if (mode == kExact) return launch_block<G, NG, 16, kExact>(a);
-  if (mode == kEarly) return launch_block<G, NG, 16, kEarly>(a);
+  if (mode == kExact) return launch_block<G, NG, W, kExact>(a);
+  if (mode == kEarly) return launch_block<G, NG, W, kEarly>(a);
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_block_any(int g, int ng, int mode, const LaunchArgs& a) {
+hipError_t launch_block_any(int g, int ng, int w, int mode, const LaunchArgs& a) {
   if (g == 4) {
-    switch (ng) {
-      case 3: return pick<4, 3>(mode, a);
-      case 4: return pick<4, 4>(mode, a);
-      case 6: return pick<4, 6>(mode, a);
-      case 8: return pick<4, 8>(mode, a);
-      case 12: return pick<4, 12>(mode, a);
-      case 16: return pick<4, 16>(mode, a);
-      default: return hipErrorInvalidValue;
-    }
+    if (w == 4 && ng == 12) return pick<4, 12, 4>(mode, a);
+    if (w == 4 && ng == 16) return pick<4, 16, 4>(mode, a);
+    if (w == 8 && ng == 12) return pick<4, 12, 8>(mode, a);
+    if (w == 8 && ng == 16) return pick<4, 16, 8>(mode, a);
+    if (w == 16 && ng == 12) return pick<4, 12, 16>(mode, a);
+    if (w == 16 && ng == 16) return pick<4, 16, 16>(mode, a);
+    return hipErrorInvalidValue;
   }
-  if (g != 1) return hipErrorInvalidValue;
+  if (g != 1 || w != 16) return hipErrorInvalidValue;
   switch (ng) {
-    case 16: return pick<1, 16>(mode, a);
-    case 32: return pick<1, 32>(mode, a);
-    case 64: return pick<1, 64>(mode, a);
+    case 16: return pick<1, 16, 16>(mode, a);
+    case 32: return pick<1, 32, 16>(mode, a);
+    case 64: return pick<1, 64, 16>(mode, a);
     default: return hipErrorInvalidValue;
   }
 }

@@ -503,3 +503,26 @@ def test_very_wide_rows_many_rows_and_unaligned_input():
     torch.cuda.synchronize()
     ev, ei = oracle.topk_exact(x[:64], k)
     assert np.array_equal(i.cpu().numpy(), ei) and np.array_equal(bits(v.cpu().numpy()), bits(ev))
+
+
+def test_more_than_2_to_31_elements():
+    # 64-bit addressing: 2^22 + 5 rows of 512 columns is just over 2^31 input elements (8 GiB)
+    R = _gpu()
+    N, M, k = (1 << 22) + 5, 512, 64
+    x = workloads.uniform(N, M, seed=99)
+    xd = torch.from_numpy(x).cuda()
+    gv, gi = R.rtopk_rowwise_exact(xd, k)
+    torch.cuda.synchronize()
+    ov, oi = oracle.topk_exact(x, k)
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    assert np.array_equal(bits(gv.cpu().numpy()), bits(ov))
+    del gv, gi
+    d = R.rtopk_maxk_dense(xd, k, 6)
+    torch.cuda.synchronize()
+    sv, si = oracle.topk_earlystop(x, k, 6)
+    tail = slice(N - 4096, N)  # the rows whose addresses lie beyond 2^31 elements
+    dt = d[tail].cpu().numpy()
+    ref = np.zeros_like(dt)
+    rows = np.arange(4096)[:, None]
+    ref[rows, si[tail]] = x[tail][rows, si[tail]]
+    assert np.array_equal(bits(dt), bits(ref))
