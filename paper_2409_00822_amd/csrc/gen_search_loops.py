@@ -118,6 +118,109 @@ __device__ __forceinline__ int search_early_asm(const float (&x)[{E}], float& lo
 """ + emit(L, outs, ins) + "  return c0;\n}\n")
 
 
+# ---------------------------------------------------------------------------------------------------
+# Row minima and maxima of R rows in one transposed reduction.
+#
+# On entry lane l holds, for each row r, mx[r] = max of its elements and nm[r] = max of its negated
+# elements.  Reducing each of the 2R values on its own costs six cross-lane steps per value.  Here every
+# step combines the upper and lower halves of TWO registers at once and keeps both results in one
+# register (one result in one half of the lanes, the other in the other half), so the number of live
+# registers halves with the lane distance: 2R -> R (distance 32, v_permlane32_swap), R -> R/2 (16,
+# v_permlane16_swap), -> R/4 (8, row_ror:8 written to the upper banks only for the second register),
+# -> R/8 (4, row_half_mirror likewise), then two quad steps on what is left.  4 vector instructions per
+# row instead of 9, and no idle slots: the independent pairs fill the two wait states that a cross-lane
+# read needs after a write.
+# Result: for row r (r < 8; sixteen rows are reduced as two batches of eight) the maximum is in lane
+# 16*(r&1) + 8*((r>>1)&1) + 4*((r>>2)&1) and the negated minimum 32 lanes above it.
+# ---------------------------------------------------------------------------------------------------
+def gen_minmax(R):
+    ins = []  # (text, dst regs, src regs)
+    mx = [f"mx{r}" for r in range(R)]
+    nm = [f"nm{r}" for r in range(R)]
+
+    def op(text, writes, reads):
+        ins.append((text, writes, reads))
+
+    for r in range(R):
+        op(f"v_permlane32_swap_b32 %[{mx[r]}], %[{nm[r]}]", [mx[r], nm[r]], [mx[r], nm[r]])
+    for r in range(R):
+        op(f"v_max_f32 %[{mx[r]}], %[{mx[r]}], %[{nm[r]}]", [mx[r]], [mx[r], nm[r]])
+    live = list(range(R))  # indices into mx
+    # distance 16
+    if len(live) > 1:
+        for i in range(0, len(live), 2):
+            a, b = mx[live[i]], mx[live[i + 1]]
+            op(f"v_permlane16_swap_b32 %[{a}], %[{b}]", [a, b], [a, b])
+        for i in range(0, len(live), 2):
+            a, b = mx[live[i]], mx[live[i + 1]]
+            op(f"v_max_f32 %[{a}], %[{a}], %[{b}]", [a], [a, b])
+        live = live[0::2]
+    cur = [mx[i] for i in live]           # registers holding the partial results
+    spare = [nm[i] for i in live]         # free registers of the same count
+    for ctrl, banks in (("row_ror:8", "0xc"), ("row_half_mirror", "0xa")):
+        if len(cur) > 1:
+            nxt, nsp = [], []
+            for i in range(0, len(cur), 2):
+                d = spare[i]
+                op(f"v_max_f32_dpp %[{d}], %[{cur[i]}], %[{cur[i]}] {ctrl} row_mask:0xf bank_mask:0xf", [d], [cur[i]])
+                nxt.append(d)
+                nsp.append(cur[i])
+            for i in range(0, len(cur), 2):
+                d = spare[i]
+                op(f"v_max_f32_dpp %[{d}], %[{cur[i + 1]}], %[{cur[i + 1]}] {ctrl} row_mask:0xf bank_mask:{banks}",
+                   [d], [cur[i + 1], d])
+            cur, spare = nxt, nsp
+        else:
+            d = spare[0]
+            op(f"v_max_f32_dpp %[{d}], %[{cur[0]}], %[{cur[0]}] {ctrl} row_mask:0xf bank_mask:0xf", [d], [cur[0]])
+            cur, spare = [d], [cur[0]]
+    for ctrl in ("quad_perm:[1,0,3,2]", "quad_perm:[2,3,0,1]"):
+        nxt, nsp = [], []
+        for i in range(len(cur)):
+            d = spare[i]
+            op(f"v_max_f32_dpp %[{d}], %[{cur[i]}], %[{cur[i]}] {ctrl} row_mask:0xf bank_mask:0xf", [d], [cur[i]])
+            nxt.append(d)
+            nsp.append(cur[i])
+        cur, spare = nxt, nsp
+    # two wait states between a write and any later read of the same register inside the block
+    lines = ['"s_nop 1\\n\\t"']  # the inputs were written by the instructions just before the block
+    last_write = {}
+    pos = 0
+    for text, writes, reads in ins:
+        need = 0
+        for rname in set(reads) | set(writes):
+            if rname in last_write:
+                need = max(need, 3 - (pos - last_write[rname]))
+        if need > 0:
+            lines.append(f'"s_nop {need - 1}\\n\\t"')
+            pos += need
+        lines.append(f'"{text}\\n\\t"')
+        for w in writes:
+            last_write[w] = pos
+        pos += 1
+    lines[-1] = lines[-1].replace("\\n\\t", "")
+    outs = [f'[mx{r}] "+v"(mx[{r}])' for r in range(R)] + [f'[nm{r}] "+v"(nm[{r}])' for r in range(R)]
+    body = "\n".join("      " + l for l in lines)
+    res = ", ".join(f"{c[:2]}[{c[2:]}]" for c in cur)
+    n_valu = len(ins)
+    getters = []
+    for r in range(R):
+        reg = cur[r // 8]
+        reg_c = f"{reg[:2]}[{reg[2:]}]"
+        lane = 16 * (r & 1) + 8 * ((r >> 1) & 1) + 4 * ((r >> 2) & 1)
+        getters.append(f"  hi[{r}] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int({reg_c}), {lane}));\n"
+                       f"  lo[{r}] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int({reg_c}), {lane + 32}) ^ (int)0x80000000);")
+    return (f"""// Row maxima and minima of {R} rows in one transposed reduction ({n_valu} vector instructions; see
+// gen_search_loops.py for the scheme).  mx[r] / nm[r]: per-lane maximum of row r's elements / of their
+// negations; both arrays are overwritten.
+__device__ __forceinline__ void wave_max_and_negmin_rows(float (&mx)[{R}], float (&nm)[{R}], float (&hi)[{R}],
+                                                         float (&lo)[{R}]) {{
+  asm volatile(
+{body}
+      : {", ".join(outs)});
+""" + "\n".join(getters) + "\n}\n")
+
+
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     text = ("// GENERATED by gen_search_loops.py -- do not edit by hand.\n"
@@ -127,6 +230,8 @@ def main():
             text += gen_exact(E, neg) + "\n" + gen_early(E, neg) + "\n"
         for dt in (1, 2):
             text += gen_exact(E, False, dt) + "\n"
+    for R in (2, 4, 8):
+        text += gen_minmax(R) + "\n"
     path = os.path.join(here, "rtopk_search_loops.inc")
     old = open(path).read() if os.path.exists(path) else None
     if old != text:

@@ -360,6 +360,63 @@ __device__ __forceinline__ void emit_selection(const float (&x)[G * NG], const u
 // (generated by gen_search_loops.py; same steps as the generic loops in select_row).
 #include "rtopk_search_loops.inc"
 
+// Per-lane part of the row minimum and maximum: mx = max of the lane's elements, nm = max of their
+// negations.  (Lanes past M hold copies of the row's first columns here, which changes neither.)
+template <int E>
+__device__ __forceinline__ void lane_max_and_negmin(const float (&xin)[E], float& mx, float& nm) {
+  if constexpr (E == 1) {
+    mx = xin[0];
+    nm = -xin[0];
+  } else if constexpr (E == 2) {
+    mx = vmax(xin[0], xin[1]);
+    nm = vmax_nn(xin[0], xin[1]);
+  } else {
+    mx = vmax3(xin[0], xin[1], xin[2]);
+    nm = vmax3_nnn(xin[0], xin[1], xin[2]);
+    int e = 3;
+#pragma unroll
+    for (; e + 1 < E; e += 2) {
+      mx = vmax3(mx, xin[e], xin[e + 1]);
+      nm = vmax3_ann(nm, xin[e], xin[e + 1]);
+    }
+    if (e < E) {
+      mx = vmax(mx, xin[e]);
+      nm = vmax_an(nm, xin[e]);
+    }
+  }
+}
+
+// Maximum and minimum of each of the R rows a wavefront holds (wave-uniform results).  Two or more rows
+// are reduced together (wave_max_and_negmin_rows: about 4 vector instructions per row instead of 9).
+template <int R, int E>
+__device__ __forceinline__ void rows_max_and_min(const float (&x)[R][E], float (&hi)[R], float (&lo)[R]) {
+  if constexpr (R == 1) {
+    float mx, nm;
+    lane_max_and_negmin<E>(x[0], mx, nm);
+    wave_max_and_negmin(mx, nm, hi[0], lo[0]);
+  } else if constexpr (R <= 8) {
+    float mx[R], nm[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) lane_max_and_negmin<E>(x[rr], mx[rr], nm[rr]);
+    wave_max_and_negmin_rows(mx, nm, hi, lo);
+  } else {
+    // eight rows at a time: the same instruction count as one wider reduction, half the registers
+    static_assert(R % 8 == 0, "rows per wavefront: 1, 2, 4, 8 or a multiple of 8");
+#pragma unroll
+    for (int b = 0; b < R; b += 8) {
+      float mx[8], nm[8], h[8], l[8];
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) lane_max_and_negmin<E>(x[b + rr], mx[rr], nm[rr]);
+      wave_max_and_negmin_rows(mx, nm, h, l);
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) {
+        hi[b + rr] = h[rr];
+        lo[b + rr] = l[rr];
+      }
+    }
+  }
+}
+
 #ifndef RTOPK_ACC_OF
 #define RTOPK_ACC_OF(E) (((E) - 3) / 3)
 #endif
@@ -383,46 +440,18 @@ __device__ __forceinline__ float midpoint_exact(float lo, float hi) {
 }
 
 //   DENSE: the result is y[] (chosen values in place, +0 elsewhere) instead of pairs staged at `stage`.
+//   row_max, row_min: the row's maximum and minimum (Alg. 1 / Alg. 2, first two steps), wave-uniform.
 template <int G, int NG, bool FULL, int MODE, bool NEG, int DT = kF32, bool DENSE = false>
 __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, int M, int k, int max_iter,
-                                          float eps_rel, uint2* stage, float (&y)[G * NG]) {
+                                          float eps_rel, uint2* stage, float (&y)[G * NG], float row_max,
+                                          float row_min) {
   constexpr int E = G * NG;
   const uint32_t stage_addr = (uint32_t)(uintptr_t)stage;  // LDS byte address
 
-  // Alg. 1 / Alg. 2, first two steps: row minimum and maximum, as max(x) and max(-x) per lane.
-  // (Lanes past M hold copies of the row's first columns here, which changes neither.)
-  float mx, nm;
-  if constexpr (E == 1) {
-    mx = xin[0];
-    nm = -xin[0];
-  } else if constexpr (E == 2) {
-    mx = vmax(xin[0], xin[1]);
-    nm = vmax_nn(xin[0], xin[1]);
-  } else {
-    mx = vmax3(xin[0], xin[1], xin[2]);
-    nm = vmax3_nnn(xin[0], xin[1], xin[2]);
-    int e = 3;
-#pragma unroll
-    for (; e + 1 < E; e += 2) {
-      mx = vmax3(mx, xin[e], xin[e + 1]);
-      nm = vmax3_ann(nm, xin[e], xin[e + 1]);
-    }
-    if (e < E) {
-      mx = vmax(mx, xin[e]);
-      nm = vmax_an(nm, xin[e]);
-    }
-  }
   // lo, hi bound the keys: for the smallest-k variant the keys are the negated values, whose maximum
   // is the negated row minimum and vice versa, so the two reduction results just swap roles.
-  float lo, hi;
-  if constexpr (NEG) {
-    float vmaxv, vminv;
-    wave_max_and_negmin(mx, nm, vmaxv, vminv);
-    hi = -vminv;
-    lo = -vmaxv;
-  } else {
-    wave_max_and_negmin(mx, nm, hi, lo);
-  }
+  float lo = NEG ? -row_max : row_min;
+  float hi = NEG ? -row_min : row_max;
 
   // From here on columns past M must never be counted or chosen: a key of -inf is below every threshold.
   float x[E];
@@ -671,13 +700,16 @@ __global__ void __launch_bounds__(256)
       for (int c = 0; c < G; ++c) x[rr][g * G + c] = v[c];
     }
   }
-  // Searching and selecting stages, row by row.
+  // Row minima and maxima of all R rows, then the searching and selecting stages row by row.
+  float row_max[R], row_min[R];
+  rows_max_and_min<R, E>(x, row_max, row_min);
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
     if (rr < nrows) {
       float unused[E];
       const int it = select_row<G, NG, FULL, MODE, NEG, DT, false>(x[rr], lane, M, k, max_iter, eps_rel,
-                                                                    stage + (size_t)rr * k, unused);
+                                                                    stage + (size_t)rr * k, unused, row_max[rr],
+                                                                    row_min[rr]);
       if constexpr (MODE == kEps) {
         if (out_iters != nullptr && lane == 0) out_iters[r0 + rr] = it;
       }
@@ -768,11 +800,14 @@ __global__ void __launch_bounds__(256)
       for (int c = 0; c < G; ++c) x[rr][g * G + c] = v[c];
     }
   }
+  float row_max[R], row_min[R];
+  rows_max_and_min<R, E>(x, row_max, row_min);
 #pragma unroll
   for (int rr = 0; rr < R; ++rr) {
     if (rr < nrows) {
       float y[E];
-      select_row<G, NG, FULL, MODE, false, kF32, true>(x[rr], lane, M, k, max_iter, 0.0f, nullptr, y);
+      select_row<G, NG, FULL, MODE, false, kF32, true>(x[rr], lane, M, k, max_iter, 0.0f, nullptr, y, row_max[rr],
+                                                       row_min[rr]);
       float* orow = out + (r0 + rr) * (int64_t)M;
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
