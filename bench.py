@@ -22,9 +22,20 @@ import sys
 import time
 
 PEAK_HBM_GBPS = 8000.0  # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the exact kernel at the headline shape, from the rocprofv3 --pmc runs summarised
-# in profiles/rtopk_wave_kernel_c1_maxk_pmc.md (not measured live: counters need the profiler).
-MEASURED_TRAFFIC_BYTES = 1342419917
+# HBM bytes per launch of the exact-mode kernel (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known
+# size), from the rocprofv3 --pmc runs summarised under profiles/ (not measured live: counters need the
+# profiler).  Keyed by (workload, k, dtype, op) at the workload's full row count.
+MEASURED_TRAFFIC = {
+    ("c1_maxk", 32, "f32", "pairs"): (1342387822, "profiles/rtopk_wave_kernel_c1_maxk_k32.md"),
+    ("c1_maxk", 32, "bf16", "pairs"): (738398038, "profiles/rtopk_wave_kernel_c1_maxk_k32dtypebf16.md"),
+    ("c1_maxk", 32, "f32", "dense"): (2147636085, "profiles/rtopk_dense_kernel_c1_maxk_k32opdense.md"),
+    ("c2_w128", 16, "f32", "pairs"): (671332109, "profiles/rtopk_wave_kernel_c2_w128_k16.md"),
+    ("c2_w512", 64, "f32", "pairs"): (2684434539, "profiles/rtopk_wave_kernel_c2_w512_k64.md"),
+    ("c2_w1024", 128, "f32", "pairs"): (5368898628, "profiles/rtopk_wave_kernel_c2_w1024_k128.md"),
+    ("c3_ties", 32, "f32", "pairs"): (2841766922, "profiles/rtopk_wave_kernel_c3_ties_k32.md"),
+    ("c4_wide", 64, "f32", "pairs"): (1107425398, "profiles/rtopk_wave_kernel_c4_wide_k64.md"),
+    ("x_wide32k", 256, "f32", "pairs"): (1090859314, "profiles/rtopk_block_kernel_x_wide32k_k256.md"),
+}
 
 
 def log(*a):
@@ -230,6 +241,7 @@ def main():
                "sample": f"all {N} rows of the same input, exact mode (nth_element), median of 8 after 1 warm-up"}
         log(f"  oracle: {t_cpu:.3f} s per pass on {cpu['cores']} threads")
 
+    traffic = MEASURED_TRAFFIC.get((args.workload, k, args.dtype, args.op), (None, None)) if N == cfg["N"] else (None, None)
     rows_per_s = N * args.steps / wall_e
     result = {
         "metric": "rows/sec, row top-k N=%d M=%d k=%d %s, exact mode (early-stop alongside)"
@@ -253,8 +265,7 @@ def main():
         "parity_vs_oracle": parity,
         "roofline": {"bound": "hbm", "achieved": algo_bytes / launch_e / 1e9, "peak": PEAK_HBM_GBPS,
                      "unit": "GB/s", "frac": algo_bytes / launch_e / 1e9 / PEAK_HBM_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES if (args.workload, N, k, args.dtype, args.op) == ("c1_maxk", 1 << 20, 32, "f32", "pairs") else None,
-                     "traffic_source": "profiles/rtopk_wave_kernel_c1_maxk_pmc.md (FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
+                     "traffic": traffic[0], "traffic_source": traffic[1],
                      "kernel": "%s, exact mode, M=%d" % ("rtopk_dense_kernel" if dense else "rtopk_wave_kernel", M),
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": launch_e * 1e6},
         "cpu_baseline": cpu,
