@@ -526,3 +526,94 @@ def test_more_than_2_to_31_elements():
     rows = np.arange(4096)[:, None]
     ref[rows, si[tail]] = x[tail][rows, si[tail]]
     assert np.array_equal(bits(dt), bits(ref))
+
+
+def test_nonfinite_inputs_terminate_and_stay_in_bounds_in_every_variant():
+    # NaN / infinities are outside the contract; every entry point must still return and write only
+    # inside its outputs (guard bands around every output buffer are checked)
+    R = _gpu()
+    pad = 2048
+
+    def guarded(n, dtype, fill):
+        buf = torch.full((n + 2 * pad,), fill, dtype=dtype, device="cuda")
+        return buf, buf[pad:pad + n]
+
+    def check(buf, fill):
+        assert (buf[:pad] == fill).all() and (buf[-pad:] == fill).all()
+
+    for N, M, k in ((500, 256, 32), (40, 4096, 64), (6, 20000, 300)):
+        x = workloads.normal(N, M, seed=87 + M)
+        x[::3, 1] = np.inf
+        x[1::3, M // 2] = -np.inf
+        x[2::3, M - 1] = np.nan
+        x[0] = np.nan
+        xd = torch.from_numpy(x).cuda()
+        vb, ov = guarded(N * k, torch.float32, 4321.0)
+        ib, oi = guarded(N * k, torch.int32, -9)
+        calls = [lambda: R.rtopk_rowwise_exact(xd, k, ov.view(N, k), oi.view(N, k)),
+                 lambda: R.rtopk_rowwise(xd, k, 9, ov.view(N, k), oi.view(N, k))]
+        if M <= 8192:
+            calls += [lambda: R.rtopk_rowwise_exact_smallest(xd, k, ov.view(N, k), oi.view(N, k)),
+                      lambda: R.rtopk_rowwise_eps(xd, k, 1e-3, ov.view(N, k), oi.view(N, k))]
+        for call in calls:
+            call()
+            torch.cuda.synchronize()
+            check(vb, 4321.0)
+            check(ib, -9)
+        if M <= 8192:
+            db, od = guarded(N * M, torch.float32, 4321.0)
+            for mi in (-1, 7):
+                R.rtopk_maxk_dense(xd, k, mi, od.view(N, M))
+                torch.cuda.synchronize()
+                check(db, 4321.0)
+            for dt in (torch.float16, torch.bfloat16):
+                x16 = xd.to(dt)
+                hb, oh = guarded(N * k, dt, 7.0)
+                name = "f16" if dt == torch.float16 else "bf16"
+                getattr(R, f"rtopk_rowwise_exact_{name}")(x16, k, oh.view(N, k), oi.view(N, k))
+                getattr(R, f"rtopk_rowwise_{name}")(x16, k, 9, oh.view(N, k), oi.view(N, k))
+                torch.cuda.synchronize()
+                check(hb, 7.0)
+                check(ib, -9)
+
+
+def test_hip_graph_replay_of_the_other_entry_points():
+    # dense, 16-bit and wide-row calls are single launches too: capture once, replay on fresh inputs
+    R = _gpu()
+    N, M, k = 3000, 256, 32
+    xs = [workloads.normal(N, M, seed=120 + i) for i in range(2)]
+    ws = [workloads.normal(16, 12288, seed=130 + i) for i in range(2)]
+    xd = torch.from_numpy(xs[0]).cuda()
+    wd = torch.from_numpy(ws[0]).cuda()
+    hd = xd.to(torch.bfloat16)
+    dense = torch.empty_like(xd)
+    hv = torch.empty((N, k), dtype=torch.bfloat16, device="cuda")
+    hi = torch.empty((N, k), dtype=torch.int32, device="cuda")
+    wv = torch.empty((16, 100), dtype=torch.float32, device="cuda")
+    wi = torch.empty((16, 100), dtype=torch.int32, device="cuda")
+    R.rtopk_maxk_dense(xd, k, -1, dense)
+    R.rtopk_rowwise_exact_bf16(hd, k, hv, hi)
+    R.rtopk_rowwise_exact(wd, 100, wv, wi)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        R.rtopk_maxk_dense(xd, k, -1, dense)
+        R.rtopk_rowwise_exact_bf16(hd, k, hv, hi)
+        R.rtopk_rowwise_exact(wd, 100, wv, wi)
+    for x, w in list(zip(xs, ws)) + [(xs[0], ws[0])]:
+        xd.copy_(torch.from_numpy(x).cuda())
+        wd.copy_(torch.from_numpy(w).cuda())
+        hd.copy_(xd.to(torch.bfloat16))
+        dense.fill_(-1.0)
+        hi.fill_(-1)
+        wi.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(dense.cpu().numpy()), bits(oracle.maxk_dense(x, k)))
+        b16 = workloads.to_bits16(x, "bf16")
+        ev, ei = oracle.topk_exact_16(b16, "bf16", k)
+        assert np.array_equal(hi.cpu().numpy(), ei)
+        assert np.array_equal(hv.view(torch.int16).cpu().numpy().view(np.uint16), ev)
+        _, wei = oracle.topk_exact(w, 100)
+        assert np.array_equal(wi.cpu().numpy(), wei)
