@@ -181,11 +181,20 @@ def main():
     wall_s, launch_s = time_calls(torch, early, args.steps, args.warmup)
     log(f"  early: {wall_s / args.steps * 1e6:.1f} us/step wall, {launch_s * 1e6:.1f} us/launch (events)")
 
+    copy_gbps = None
     if args.with_copy:
         y = torch.empty_like(x)
         for _ in range(5):
             y.copy_(x)
         torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(20):
+            y.copy_(x)
+        b.record()
+        torch.cuda.synchronize()
+        copy_gbps = 2 * x.numel() * x.element_size() / (a.elapsed_time(b) * 1e-3 / 20) / 1e9
+        log(f"  device copy of the input (read + write): {a.elapsed_time(b) / 20 * 1e3:.1f} us, {copy_gbps:.0f} GB/s")
         del y
 
     parity = None
@@ -267,7 +276,8 @@ def main():
                      "unit": "GB/s", "frac": algo_bytes / launch_e / 1e9 / PEAK_HBM_GBPS,
                      "traffic": traffic[0], "traffic_source": traffic[1],
                      "kernel": "%s, exact mode, M=%d" % ("rtopk_dense_kernel" if dense else "rtopk_wave_kernel", M),
-                     "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": launch_e * 1e6},
+                     "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_us": launch_e * 1e6,
+                     "device_copy_gbps": copy_gbps},
         "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)

@@ -617,3 +617,65 @@ def test_hip_graph_replay_of_the_other_entry_points():
         assert np.array_equal(hv.view(torch.int16).cpu().numpy().view(np.uint16), ev)
         _, wei = oracle.topk_exact(w, 100)
         assert np.array_equal(wi.cpu().numpy(), wei)
+
+
+def test_randomised_shapes_modes_and_entry_points():
+    # 300 seeded draws of (N, M, k, mode, entry point, value distribution): every load path, ragged
+    # widths, every output form, each compared with the oracle bit for bit
+    R = _gpu()
+    rng = np.random.Generator(np.random.Philox(20240901))
+    widths = [1, 2, 3, 31, 64, 65, 127, 128, 129, 255, 256, 257, 384, 500, 512, 640, 768, 1000, 1024, 1028, 1536, 2047,
+              2048, 2500, 3072, 4096, 5000, 6144, 7777, 8192, 8200, 10000, 16384, 24576, 33000]
+    for it in range(300):
+        M = int(widths[rng.integers(len(widths))]) if rng.random() < 0.7 else int(rng.integers(1, 9000))
+        N = int(rng.integers(1, 40 if M > 2048 else 300))
+        k = int(rng.integers(1, M + 1)) if rng.random() < 0.5 else int(max(1, min(M, rng.integers(1, 65))))
+        gen = rng.integers(4)
+        seed = int(rng.integers(1 << 30))
+        if gen == 0:
+            x = workloads.normal(N, M, seed)
+        elif gen == 1:
+            x = workloads.normal_ties(N, M, seed, p=0.3)
+        elif gen == 2:
+            x = workloads.small_ints(N, M, seed, span=int(rng.integers(1, 30)))
+        else:
+            x = workloads.laplace(N, M, seed)
+        mi = int(rng.integers(0, 20))
+        kinds = ["exact", "early"]
+        if M <= 8192:
+            kinds += ["smallest_exact", "smallest_early", "eps", "dense_exact", "dense_early", "f16", "bf16"]
+        if M <= 256:
+            kinds += ["u8_exact", "u8_early"]
+        kind = kinds[rng.integers(len(kinds))]
+        tag = f"draw {it}: N={N} M={M} k={k} {kind} max_iter={mi} gen={gen} seed={seed}"
+        if kind == "exact":
+            assert_parity(R, x, k, "exact", tag=tag)
+        elif kind == "early":
+            assert_parity(R, x, k, "early", mi, tag=tag)
+        elif kind == "u8_exact":
+            assert_parity(R, x, k, "exact", u8=True, tag=tag)
+        elif kind == "u8_early":
+            assert_parity(R, x, k, "early", mi, u8=True, tag=tag)
+        elif kind == "smallest_exact":
+            assert_smallest_parity(R, x, k, "exact", tag=tag)
+        elif kind == "smallest_early":
+            assert_smallest_parity(R, x, k, "early", mi, tag=tag)
+        elif kind == "eps":
+            assert_eps_parity(R, x, k, float(10.0 ** -rng.integers(1, 8)), tag=tag)
+        elif kind == "dense_exact":
+            assert_dense_parity(R, x, k, -1, tag=tag)
+        elif kind == "dense_early":
+            assert_dense_parity(R, x, k, mi, tag=tag)
+        else:
+            b = workloads.to_bits16(x, kind)
+            xd = torch.from_numpy(b.view(np.int16)).cuda().view(torch.float16 if kind == "f16" else torch.bfloat16)
+            exact = rng.random() < 0.5
+            if exact:
+                gv, gi = getattr(R, f"rtopk_rowwise_exact_{kind}")(xd, k)
+                ov, oi = oracle.topk_exact_16(b, kind, k)
+            else:
+                gv, gi = getattr(R, f"rtopk_rowwise_{kind}")(xd, k, mi)
+                ov, oi = oracle.topk_earlystop_16(b, kind, k, mi)
+            torch.cuda.synchronize()
+            assert np.array_equal(gi.cpu().numpy(), oi), tag
+            assert np.array_equal(gv.view(torch.int16).cpu().numpy().view(np.uint16), ov), tag
