@@ -679,3 +679,25 @@ def test_randomised_shapes_modes_and_entry_points():
             torch.cuda.synchronize()
             assert np.array_equal(gi.cpu().numpy(), oi), tag
             assert np.array_equal(gv.view(torch.int16).cpu().numpy().view(np.uint16), ov), tag
+
+
+def test_exit_iteration_statistics_of_table5_on_the_gpu():
+    # Table 5 (Appendix A) reproduced from the kernel's own iteration output at epsilon = 0, including
+    # the closed form of Eq. 4 sitting slightly above the measured mean, for rows up to 8192 wide
+    from conftest import read_table
+
+    R = _gpu()
+    header, rows = read_table("table5_exit_cumulative.txt")
+    cols = [tuple(int(a) for a in h.split("_")) for h in header[1:]]
+    for col, (M, k) in enumerate(cols):
+        x = workloads.normal(10000, M, seed=3000 + col)
+        _, _, it = R.rtopk_rowwise_eps(torch.from_numpy(x).cuda(), k, 0.0, want_iters=True)
+        it = it.cpu().numpy()
+        for row in rows:
+            paper = float(row[1 + col])
+            if row[0] == "avg":
+                assert abs(float(it.mean()) - paper) < 0.12, (M, k, it.mean(), paper)
+            elif row[0] == "En":
+                assert 0.0 < paper - float(it.mean()) < 0.6, (M, k)
+            else:
+                assert abs(float((it <= int(row[0])).mean() * 100.0) - paper) < 2.6, (M, k, row[0])
