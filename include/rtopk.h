@@ -27,9 +27,9 @@
  *    negative RTOPK_ERR_* code; every argument check happens on the host before any launch, and on
  *    error nothing was enqueued.  Faults of the asynchronous work surface at the caller's next
  *    synchronisation, as with any HIP launch.
- *  - Limits: 1 <= k <= M; 0 <= N; N * M and N * k must fit in int64_t.  rtopk_rowwise and
- *    rtopk_rowwise_exact accept M <= rtopk_max_m() = 65536 (rows wider than 8192 columns are handled by
- *    one workgroup per row, and then N < 2^31); every other entry point accepts M <= 8192.
+ *  - Limits: 1 <= k <= M <= rtopk_max_m() = 65536 (256 in the *_u8 variants); 0 <= N; N * M and N * k
+ *    must fit in int64_t.  Rows wider than 8192 columns are handled by one workgroup per row, and
+ *    then N < 2^31.
  */
 #ifndef RTOPK_H_
 #define RTOPK_H_
@@ -45,7 +45,7 @@ enum {
   RTOPK_ERR_NULL_POINTER = -1,  /* a data pointer is NULL while N > 0 */
   RTOPK_ERR_BAD_SHAPE = -2,     /* N < 0, M < 1, k < 1 or k > M */
   RTOPK_ERR_BAD_MAX_ITER = -3,  /* max_iter < 0 */
-  RTOPK_ERR_M_TOO_LARGE = -4,   /* M beyond the entry point's limit (see "Limits"), or M > 256 in a *_u8 variant */
+  RTOPK_ERR_M_TOO_LARGE = -4,   /* M > rtopk_max_m(), or M > 256 in a *_u8 variant */
   RTOPK_ERR_MISALIGNED = -5,    /* a pointer is not aligned to its element size */
   RTOPK_ERR_LAUNCH = -6,        /* the HIP runtime refused the launch */
   RTOPK_ERR_BAD_EPSILON = -7    /* eps_rel is negative or NaN */
@@ -137,7 +137,7 @@ const char* rtopk_status_string(int status);
 /* Library version, major * 10000 + minor * 100 + patch. */
 int rtopk_version(void);
 
-/* Largest supported row width M (of rtopk_rowwise and rtopk_rowwise_exact; see "Limits"). */
+/* Largest supported row width M. */
 int rtopk_max_m(void);
 
 #ifdef __cplusplus

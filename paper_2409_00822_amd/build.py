@@ -13,7 +13,8 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "librtopk.so")
 
 SOURCES = ["rtopk_api.hip", "rtopk_inst_g4_exact.hip", "rtopk_inst_g4_early.hip", "rtopk_inst_g4_eps.hip",
-           "rtopk_inst_small.hip", "rtopk_inst_h16_exact.hip", "rtopk_inst_h16_early.hip", "rtopk_inst_dense.hip", "rtopk_inst_block.hip"]
+           "rtopk_inst_small.hip", "rtopk_inst_h16_exact.hip", "rtopk_inst_h16_early.hip", "rtopk_inst_dense.hip", "rtopk_inst_block.hip", "rtopk_inst_block_var.hip",
+           "rtopk_inst_block_dense.hip", "rtopk_inst_block_h16.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -35,7 +36,7 @@ def build(verbose: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     # regenerate the inline-assembly search loops (a no-op when the committed file is current)
     subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_search_loops.py")], stdout=subprocess.DEVNULL)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH])
     if verbose:

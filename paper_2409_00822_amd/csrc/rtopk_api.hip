@@ -9,9 +9,9 @@
 
 namespace {
 
-constexpr int kMaxM = 65536;     // rtopk_rowwise / rtopk_rowwise_exact (one workgroup per row beyond kMaxWaveM)
-constexpr int kMaxWaveM = 8192;  // widest row one wavefront holds in registers; the limit of every other entry point
-constexpr int kVersion = 400;  // 0.4.0
+constexpr int kMaxM = 65536;     // one workgroup per row beyond kMaxWaveM
+constexpr int kMaxWaveM = 8192;  // widest row one wavefront holds in registers
+constexpr int kVersion = 500;  // 0.5.0
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -26,8 +26,7 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
   if (mode == rtopk::kEarly && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
   if (mode == rtopk::kEps && !(eps_rel >= 0.0f)) return RTOPK_ERR_BAD_EPSILON;
-  const bool plain = dtype == rtopk::kF32 && !u8 && !smallest && mode != rtopk::kEps;
-  if (M > (plain ? kMaxM : kMaxWaveM) || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
   if (N == 0) return RTOPK_OK;
   if (!in || !out_vals || !out_idx) return RTOPK_ERR_NULL_POINTER;
   if (!aligned(in, esz) || !aligned(out_vals, esz) || (!u8 && !aligned(out_idx, 4)) || !aligned(out_iters, 4))
@@ -57,16 +56,23 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   hipError_t err;
   if (M > kMaxWaveM) {
     if (N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row: the grid holds 2^31 - 1 rows
+    // a lane holds up to 64 values: 4 wavefronts up to 16384 columns, 8 up to 32768, 16 beyond
     int g = 1, ng = 16, w = 16;
-    if (M % 4 == 0 && aligned(in, 16)) {
-      // a lane holds up to 64 values: 4 wavefronts up to 16384 columns, 8 up to 32768, 16 beyond
+    const bool plain = dtype == rtopk::kF32 && !smallest && mode != rtopk::kEps;
+    if (dtype == rtopk::kF32 && M % 4 == 0 && aligned(in, 16)) {
       g = 4;
       w = M <= 16384 ? 4 : (M <= 32768 ? 8 : 16);
-      ng = M <= 64 * w * 4 * 12 ? 12 : 16;
+      ng = (plain && M <= 64 * w * 4 * 12) ? 12 : 16;
+    } else if (dtype != rtopk::kF32 && M % 8 == 0 && aligned(in, 16)) {
+      g = 8;
+      w = M <= 16384 ? 4 : (M <= 32768 ? 8 : 16);
+      ng = 8;
     } else {
       while (1024 * ng < M) ng <<= 1;
     }
-    err = rtopk::launch_block_any(g, ng, w, mode, a);
+    err = dtype != rtopk::kF32 ? rtopk::launch_block_h16(dtype, g, ng, w, mode, a)
+          : plain              ? rtopk::launch_block_plain(g, ng, w, mode, a)
+                               : rtopk::launch_block_variant(g, ng, w, mode, smallest, a);
   } else if (dtype != rtopk::kF32) {
     // 16-bit rows: the widest load whose 64 lanes the row still fills, else the scalar-load fallback
     int g = 1, ng = 1;
@@ -177,7 +183,7 @@ int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k
 
 int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out, void* stream) {
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
-  if (M > kMaxWaveM) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > kMaxM) return RTOPK_ERR_M_TOO_LARGE;
   if (N == 0) return RTOPK_OK;
   if (!in || !out) return RTOPK_ERR_NULL_POINTER;
   if (!aligned(in, 4) || !aligned(out, 4)) return RTOPK_ERR_MISALIGNED;
@@ -195,6 +201,19 @@ int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t m
   a.out_vals = out;
   a.stream = static_cast<hipStream_t>(stream);
   int g = 1, ng = 1;
+  if (M > kMaxWaveM) {
+    if (N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row
+    int w = 16;
+    ng = 16;
+    if (M % 4 == 0 && aligned(in, 16) && aligned(out, 16)) {
+      g = 4;
+      w = M <= 16384 ? 4 : (M <= 32768 ? 8 : 16);
+    } else {
+      while (1024 * ng < M) ng <<= 1;
+    }
+    const hipError_t e = rtopk::launch_block_dense(g, ng, w, mode, a);
+    return e == hipSuccess ? RTOPK_OK : RTOPK_ERR_LAUNCH;
+  }
   if (M > 128 && M % 4 == 0 && aligned(in, 16) && aligned(out, 16)) {
     static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
     g = 4;
@@ -220,7 +239,7 @@ const char* rtopk_status_string(int status) {
     case RTOPK_ERR_NULL_POINTER: return "null data pointer with N > 0";
     case RTOPK_ERR_BAD_SHAPE: return "bad shape: need N >= 0 and 1 <= k <= M";
     case RTOPK_ERR_BAD_MAX_ITER: return "max_iter must be >= 0";
-    case RTOPK_ERR_M_TOO_LARGE: return "M exceeds the supported row width (65536 for fp32 rows with int32 columns, 8192 otherwise, 256 for uint8 columns)";
+    case RTOPK_ERR_M_TOO_LARGE: return "M exceeds the supported row width (65536; 256 for uint8 columns)";
     case RTOPK_ERR_MISALIGNED: return "pointer not aligned to its element size";
     case RTOPK_ERR_LAUNCH: return "the HIP runtime refused the launch";
     case RTOPK_ERR_BAD_EPSILON: return "eps_rel must be >= 0";

@@ -15,6 +15,10 @@
 //
 // Every wavefront evaluates the same thresholds on the same totals, so all of them take the same
 // branches and reach the same barriers; the trip count of the search is uniform over the workgroup.
+//
+// Template parameters beyond the layout, all with the meaning they have in rtopk_kernel.hpp:
+//   MODE (kEarly / kExact / kEps), NEG (the k smallest), DT (fp32, half or bfloat16 rows),
+//   DENSE (chosen values in place and zero elsewhere instead of (value, column) pairs; fp32 only).
 #pragma once
 
 #include "rtopk_kernel.hpp"
@@ -31,13 +35,42 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
   return v;
 }
 
-template <int G, int NG, int W, int MODE>
+// In the lanes whose bit is set in `mask`: the 32-bit (or, for 16-bit rows, the narrowed 16-bit) value
+// goes to vals + off_v bytes and the column to cols + off_c bytes.  Both bases are wave-uniform; the
+// kernel's control flow is uniform over the wavefront, so EXEC is all ones on entry and restored so.
+template <int DT>
+__device__ __forceinline__ void store_pair_masked(uint64_t mask, void* vals, uint32_t off_v, uint32_t value_bits,
+                                                  int32_t* cols, uint32_t off_c, int32_t col) {
+  if constexpr (DT == kF32) {
+    asm volatile(
+        "s_mov_b64 exec, %0\n\t"
+        "global_store_dword %1, %2, %3\n\t"
+        "global_store_dword %4, %5, %6\n\t"
+        "s_mov_b64 exec, -1"
+        :
+        : "s"(mask), "v"(off_v), "v"(value_bits), "s"(vals), "v"(off_c), "v"(col), "s"(cols)
+        : "memory");
+  } else {
+    asm volatile(
+        "s_mov_b64 exec, %0\n\t"
+        "global_store_short %1, %2, %3\n\t"
+        "global_store_dword %4, %5, %6\n\t"
+        "s_mov_b64 exec, -1"
+        :
+        : "s"(mask), "v"(off_v), "v"(value_bits), "s"(vals), "v"(off_c), "v"(col), "s"(cols)
+        : "memory");
+  }
+}
+
+template <int G, int NG, int W, int MODE, bool NEG, int DT, bool DENSE>
 __global__ void __launch_bounds__(W * kWave)
-    rtopk_block_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter,
-                       float* __restrict__ out_vals, int32_t* __restrict__ out_idx) {
+    rtopk_block_kernel(const void* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
+                       void* __restrict__ out_vals, int32_t* __restrict__ out_idx, int32_t* __restrict__ out_iters) {
+  static_assert(!DENSE || DT == kF32, "the dense form is built for fp32 rows");
   constexpr int E = G * NG;
   constexpr int T = NG * W;  // (group, wavefront) cells of a row, in column order
   constexpr int CPL = (T + kWave - 1) / kWave;  // cells per lane when one wavefront scans the table
+  using ElemT = typename std::conditional<DT == kF32, float, uint16_t>::type;
   __shared__ float s_hi[W], s_nlo[W];  // per-wavefront maximum and negated minimum
   __shared__ int s_cnt[2][W];          // per-wavefront counts of a search step, double buffered
   __shared__ int s_tab[2][T];          // candidates per cell of class A / class B, then their exclusive prefixes
@@ -46,7 +79,7 @@ __global__ void __launch_bounds__(W * kWave)
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int64_t r = blockIdx.x;
   if (r >= N) return;
-  const float* row = in + r * (int64_t)M;
+  const ElemT* row = static_cast<const ElemT*>(in) + r * (int64_t)M;
 
   // Loading stage.  Lanes past M load the row's first columns (in bounds, cannot change min or max).
   float x[E];
@@ -54,26 +87,22 @@ __global__ void __launch_bounds__(W * kWave)
   for (int g = 0; g < NG; ++g) {
     const int col0 = ((g * W + wave) * kWave + lane) * G;
     float v[G];
-    load_group<kF32, G>(row, col0 < M ? col0 : 0, v);
+    load_group<DT, G>(row, col0 < M ? col0 : 0, v);
 #pragma unroll
     for (int c = 0; c < G; ++c) x[g * G + c] = v[c];
   }
 
   // Row minimum and maximum: per lane, per wavefront, then over the W wavefronts through LDS.
-  float mx = x[0], nm = -x[0];
-#pragma unroll
-  for (int e = 1; e < E; ++e) {
-    mx = vmax(mx, x[e]);
-    nm = vmax_an(nm, x[e]);
-  }
   float hi, lo;
-  wave_max_and_negmin(mx, nm, hi, lo);
-  if (lane == 0) {
-    s_hi[wave] = hi;
-    s_nlo[wave] = -lo;
-  }
-  __syncthreads();
   {
+    float mx, nm, wmax, wmin;
+    lane_max_and_negmin<E>(x, mx, nm);
+    wave_max_and_negmin(mx, nm, wmax, wmin);
+    if (lane == 0) {
+      s_hi[wave] = wmax;
+      s_nlo[wave] = -wmin;
+    }
+    __syncthreads();
     float a = s_hi[0], b = s_nlo[0];
 #pragma unroll
     for (int w = 1; w < W; ++w) {
@@ -81,24 +110,29 @@ __global__ void __launch_bounds__(W * kWave)
       b = vmax(b, s_nlo[w]);
     }
     // every lane holds the same two values; saying so lets the search loop branch on scalar conditions
-    hi = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a)));
-    lo = -__int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(b)));
+    const float row_max = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a)));
+    const float row_min = -__int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(b)));
+    // bounds of the keys (negated values for the k smallest)
+    hi = NEG ? -row_min : row_max;
+    lo = NEG ? -row_max : row_min;
   }
 
-  // From here on columns past M must never be counted or chosen.
+  // From here on columns past M must never be counted or chosen: their key is -inf.
+  if (M != kWave * G * NG * W) {  // uniform: full-width rows skip the masking
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int col0 = (((e / G) * W + wave) * kWave + lane) * G;
-    x[e] = col0 < M ? x[e] : -__builtin_inff();
+    for (int e = 0; e < E; ++e) {
+      const int col0 = (((e / G) * W + wave) * kWave + lane) * G;
+      x[e] = col0 < M ? x[e] : (NEG ? __builtin_inff() : -__builtin_inff());
+    }
   }
 
-  // cnt = #{row elements >= t}: this wavefront's share, then the sum over the workgroup.  `step`
-  // selects the half of s_cnt that is written; one barrier per step is enough because a half is not
-  // written again before every wavefront has passed the next barrier.
+  // cnt = #{row elements with key >= t}: this wavefront's share, then the sum over the workgroup.
+  // `step` selects the half of s_cnt that is written; one barrier per step is enough because a half is
+  // not written again before every wavefront has passed the next barrier.
   constexpr int ACC = E <= 8 ? 0 : (E - 3) / 3;
   int step = 0;
   auto count = [&](float t) -> int {
-    const int mine = count_ge_wide<E, ACC, false>(x, t);
+    const int mine = count_ge_wide<E, ACC, NEG>(x, t);
     const int p = step & 1;
     ++step;
     if (lane == 0) s_cnt[p][wave] = mine;
@@ -107,31 +141,50 @@ __global__ void __launch_bounds__(W * kWave)
   };
 
   // The selection is described by two classes of elements and a limit for each:
-  //   class A: x >= tA, the first limA of them in column order are chosen;
-  //   class B: tB <= x < tA, the first limB of them are chosen (only after a converged search).
+  //   class A: key >= tA, the first limA of them in column order are chosen;
+  //   class B: tB <= key < tA, the first limB of them are chosen (only after a converged search).
   float tA, tB = 0.0f;
   int limA = k, limB = 0;
-  if constexpr (MODE == kExact) {
-    // Algorithm 1 at epsilon = 0; termination and collection as in select_row.
+  if constexpr (MODE == kExact || MODE == kEps) {
+    // Algorithm 1; termination, collection and iteration numbering as in select_row.
     bool hit = false;
-    float thres = lo, seen = lo;
-    for (;;) {
-      thres = (lo + hi) * 0.5f;
-      if (!(thres < seen || thres > seen)) break;
-      seen = thres;
-      int cnt = count(thres);
-      if (cnt == k) {
-        hit = true;
-        break;
+    float thres = lo;
+    if constexpr (MODE == kExact) {
+      float seen = lo;
+      for (;;) {
+        thres = midpoint_exact<DT>(lo, hi);
+        if (!(thres < seen || thres > seen)) break;
+        seen = thres;
+        int cnt = count(thres);
+        if (cnt == k) {
+          hit = true;
+          break;
+        }
+        move_bound(lo, hi, thres, cnt, k);
+        thres = midpoint_exact<DT>(lo, hi);
+        cnt = count(thres);
+        if (cnt == k) {
+          hit = true;
+          break;
+        }
+        move_bound(lo, hi, thres, cnt, k);
       }
-      move_bound(lo, hi, thres, cnt, k);
-      thres = (lo + hi) * 0.5f;
-      cnt = count(thres);
-      if (cnt == k) {
-        hit = true;
-        break;
+    } else {
+      const float eps = eps_rel * __builtin_fabsf(hi);
+      int steps = 0;
+      while (hi - lo > eps) {
+        const float mid = (lo + hi) * 0.5f;
+        if (!(mid > lo && mid < hi)) break;
+        thres = mid;
+        ++steps;
+        const int cnt = count(thres);
+        if (cnt == k) {
+          hit = true;
+          break;
+        }
+        move_bound(lo, hi, thres, cnt, k);
       }
-      move_bound(lo, hi, thres, cnt, k);
+      if (out_iters != nullptr && threadIdx.x == 0) out_iters[r] = hit ? steps : steps + 1;
     }
     if (hit) {
       tA = thres;
@@ -143,7 +196,7 @@ __global__ void __launch_bounds__(W * kWave)
       limB = k - limA;
     }
   } else {
-    // Algorithm 2: max_iter steps (fewer once a step counts exactly k), then the first k of x >= lo.
+    // Algorithm 2: max_iter steps (fewer once a step counts exactly k), then the first k of key >= lo.
     for (int it = 0; it < max_iter; ++it) {
       const float thres = (lo + hi) * 0.5f;
       const int cnt = count(thres);
@@ -160,7 +213,7 @@ __global__ void __launch_bounds__(W * kWave)
     int nA = 0, nB = 0;
 #pragma unroll
     for (int c = 0; c < G; ++c) {
-      const float v = x[g * G + c];
+      const float v = keyof<NEG>(x[g * G + c]);
       nA += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v >= tA));
       if (has_b) nB += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v >= tB && !(v >= tA)));
     }
@@ -190,15 +243,16 @@ __global__ void __launch_bounds__(W * kWave)
     }
   }
   __syncthreads();
-  // Part 3: every wavefront ranks its own elements and writes the chosen pairs straight to the
-  // outputs (k can be far larger than LDS could stage; consecutive ranks fall on consecutive lanes,
-  // so the stores are still mostly coalesced).
-  float* ov = out_vals + r * (int64_t)k;
-  int32_t* oi = out_idx + r * (int64_t)k;
+
+  // Part 3: every wavefront ranks its own elements.  Pairs go straight to the outputs at 4 (or 2) bytes
+  // times their rank (k can be far larger than LDS could stage; consecutive ranks fall on consecutive
+  // lanes, so the stores are still mostly coalesced); the dense form keeps or zeroes each element in
+  // place and stores the row with the accesses it was loaded with.
+  using OutT = typename std::conditional<DT == kF32, uint32_t, uint16_t>::type;  // value bits as stored
+  OutT* ov = static_cast<OutT*>(out_vals) + r * (int64_t)(DENSE ? M : k);
+  int32_t* oi = DENSE ? nullptr : out_idx + r * (int64_t)k;
   if (!has_b) {
-    // One class: rank = cell prefix + chosen elements in lower lanes + own earlier elements; the pair
-    // goes to byte offset 4*rank of both outputs under EXEC = (candidate and rank < limA).  The
-    // kernel's control flow is uniform over the wavefront, so EXEC is all ones here and is restored so.
+    // One class: rank = cell prefix + chosen elements in lower lanes + own earlier elements.
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       int ln = lane;  // opaque per group: keeps the column numbers of all groups from being hoisted
@@ -207,23 +261,26 @@ __global__ void __launch_bounds__(W * kWave)
       uint32_t pos = (uint32_t)__builtin_amdgcn_readfirstlane(s_tab[0][g * W + wave]);
 #pragma unroll
       for (int c = 0; c < G; ++c) {
-        m[c] = __builtin_amdgcn_ballot_w64(x[g * G + c] >= tA);
+        m[c] = __builtin_amdgcn_ballot_w64(keyof<NEG>(x[g * G + c]) >= tA);
         pos = lanes_below(m[c], pos);
       }
+      const int col0 = ((g * W + wave) * kWave + ln) * G;
+      float y[G];
 #pragma unroll
       for (int c = 0; c < G; ++c) {
         const uint64_t mk = m[c] & __builtin_amdgcn_ballot_w64(pos < (uint32_t)limA);
-        const uint32_t off = pos * 4u;
-        const int32_t col = ((g * W + wave) * kWave + ln) * G + c;
-        asm volatile(
-            "s_mov_b64 exec, %0\n\t"
-            "global_store_dword %1, %2, %3\n\t"
-            "global_store_dword %1, %4, %5\n\t"
-            "s_mov_b64 exec, -1"
-            :
-            : "s"(mk), "v"(off), "v"(x[g * G + c]), "s"(ov), "v"(col), "s"(oi)
-            : "memory");
+        if constexpr (DENSE) {
+          y[c] = keep_where(x[g * G + c], mk);
+        } else {
+          const uint32_t fb = __float_as_uint(x[g * G + c]);
+          uint32_t bits = fb;
+          if constexpr (DT != kF32) bits = narrow_bits<DT>(fb);
+          store_pair_masked<DT>(mk, ov, pos * (uint32_t)sizeof(OutT), bits, oi, pos * 4u, col0 + c);
+        }
         if (c + 1 < G) pos = add_mask_bit(pos, m[c]);
+      }
+      if constexpr (DENSE) {
+        if (col0 < M) store_group<G>(reinterpret_cast<float*>(ov) + col0, y);
       }
       if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);
     }
@@ -237,34 +294,47 @@ __global__ void __launch_bounds__(W * kWave)
     bool a[G], b[G];
 #pragma unroll
     for (int c = 0; c < G; ++c) {
-      const float v = x[g * G + c];
+      const float v = keyof<NEG>(x[g * G + c]);
       a[c] = v >= tA;
       b[c] = v >= tB && !a[c];
       posA = lanes_below(__builtin_amdgcn_ballot_w64(a[c]), posA);
       posB = lanes_below(__builtin_amdgcn_ballot_w64(b[c]), posB);
     }
+    const int col0 = ((g * W + wave) * kWave + lane) * G;
+    float y[G];
 #pragma unroll
     for (int c = 0; c < G; ++c) {
       const uint32_t selA = posA < (uint32_t)limA ? posA : (uint32_t)limA;  // chosen A's before this element
       const uint32_t selB = posB < (uint32_t)limB ? posB : (uint32_t)limB;
-      if ((a[c] && posA < (uint32_t)limA) || (b[c] && posB < (uint32_t)limB)) {
-        const uint32_t pos = selA + selB;
-        ov[pos] = x[g * G + c];
-        oi[pos] = ((g * W + wave) * kWave + lane) * G + c;
+      const bool chosen = (a[c] && posA < (uint32_t)limA) || (b[c] && posB < (uint32_t)limB);
+      if constexpr (DENSE) {
+        y[c] = chosen ? x[g * G + c] : 0.0f;
+      } else {
+        if (chosen) {
+          const uint32_t pos = selA + selB;
+          const uint32_t fb = __float_as_uint(x[g * G + c]);
+          uint32_t bits = fb;
+          if constexpr (DT != kF32) bits = narrow_bits<DT>(fb);
+          ov[pos] = (OutT)bits;
+          oi[pos] = col0 + c;
+        }
       }
       posA += a[c] ? 1u : 0u;
       posB += b[c] ? 1u : 0u;
+    }
+    if constexpr (DENSE) {
+      if (col0 < M) store_group<G>(reinterpret_cast<float*>(ov) + col0, y);
     }
     if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-template <int G, int NG, int W, int MODE>
+template <int G, int NG, int W, int MODE, bool NEG = false, int DT = kF32, bool DENSE = false>
 hipError_t launch_block(const LaunchArgs& a) {
   if (a.N > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((rtopk_block_kernel<G, NG, W, MODE>), dim3((unsigned)a.N), dim3(W * kWave), 0, a.stream,
-                     static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter, static_cast<float*>(a.out_vals),
-                     static_cast<int32_t*>(a.out_idx));
+  hipLaunchKernelGGL((rtopk_block_kernel<G, NG, W, MODE, NEG, DT, DENSE>), dim3((unsigned)a.N), dim3(W * kWave), 0,
+                     a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
+                     static_cast<int32_t*>(a.out_idx), a.out_iters);
   return hipGetLastError();
 }
 

@@ -43,9 +43,13 @@ hipError_t launch_g4_eps(int ng, bool full, const LaunchArgs& a);  // int32 colu
 // (8, 4, 2 or 1: M % g == 0 and `in` aligned to 2*g bytes), ng = loads per lane (M <= 64*g*ng).
 hipError_t launch_h16_exact(int dtype, int g, int ng, bool full, const LaunchArgs& a);
 hipError_t launch_h16_early(int dtype, int g, int ng, bool full, const LaunchArgs& a);
-// Rows wider than 8192 columns (fp32, int32 columns, kEarly / kExact): one workgroup of w wavefronts
-// per row.  g = 4 (M % 4 == 0, `in` 16-byte aligned) or 1; ng = loads per lane (M <= 64*w*g*ng).
-hipError_t launch_block_any(int g, int ng, int w, int mode, const LaunchArgs& a);
+// Rows wider than 8192 columns: one workgroup of w wavefronts per row (int32 columns).  g = elements per
+// load (4 for fp32 / 8 for 16-bit rows: M % g == 0 and 16-byte aligned pointers; else 1), ng = loads per
+// lane, M <= 64*w*g*ng.
+hipError_t launch_block_plain(int g, int ng, int w, int mode, const LaunchArgs& a);                   // fp32, kEarly / kExact
+hipError_t launch_block_variant(int g, int ng, int w, int mode, bool smallest, const LaunchArgs& a);  // fp32: kEps, or the k smallest
+hipError_t launch_block_dense(int g, int ng, int w, int mode, const LaunchArgs& a);                   // fp32 dense output
+hipError_t launch_block_h16(int dtype, int g, int ng, int w, int mode, const LaunchArgs& a);          // half / bfloat16 rows
 // Dense-output form (fp32; a.out_vals is the [N][M] output, a.out_idx unused).  g, ng, full as above;
 // mode kEarly or kExact.
 hipError_t launch_dense_any(int g, int ng, bool full, int mode, const LaunchArgs& a);

@@ -64,8 +64,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert f(p, 4, 65537, 32, 8, p, p, None) == -4
     assert fe(p, 4, 70000, 32, p, p, None) == -4
     assert f(p, 2 ** 31, 9000, 32, 8, p, p, None) == -2   # one workgroup per row beyond 8192 columns: 2^31 - 1 rows
-    assert lib.rtopk_rowwise_smallest(p, 4, 8200, 32, 8, p, p, None) == -4
-    assert lib.rtopk_rowwise_exact_smallest(p, 4, 8200, 32, p, p, None) == -4
+    assert lib.rtopk_rowwise_smallest(p, 4, 65540, 32, 8, p, p, None) == -4
+    assert lib.rtopk_rowwise_exact_smallest(p, 4, 65540, 32, p, p, None) == -4
     assert lib.rtopk_rowwise_u8(p, 4, 260, 32, 8, p, p, None) == -4
     assert lib.rtopk_rowwise_exact_u8(p, 4, 260, 32, p, p, None) == -4
     fz = lib.rtopk_rowwise_eps
@@ -75,7 +75,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fz(p, 4, 256, 32, float("nan"), p, p, None, None) == -7
     assert fz(p, 0, 256, 32, 0.5, None, None, None, None) == 0
     assert fz(p, 4, 256, 32, 0.5, p, p, p + 2, None) == -5
-    assert fz(p, 4, 8200, 32, 0.5, p, p, None, None) == -4
+    assert fz(p, 4, 65540, 32, 0.5, p, p, None, None) == -4
     assert f(p + 2, 4, 256, 32, 8, p, p, None) == -5
     assert f(p, 4, 256, 32, 8, p + 1, p, None) == -5
     assert f(p, 4, 256, 32, 8, p, p + 2, None) == -5
@@ -84,7 +84,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fd(None, 4, 256, 32, -1, p, None) == -1
     assert fd(p, 4, 256, 32, 8, None, None) == -1
     assert fd(p, 4, 256, 300, 8, p, None) == -2
-    assert fd(p, 4, 9000, 32, 8, p, None) == -4
+    assert fd(p, 4, 70000, 32, 8, p, None) == -4
     assert fd(p + 2, 4, 256, 32, 8, p, None) == -5
     assert fd(p, 4, 256, 32, 8, p + 3, None) == -5
     # rows stored in 16 bits: 2-byte alignment is enough for values, the other checks are shared
@@ -96,10 +96,10 @@ def test_argument_errors_are_reported_before_any_launch(lib):
         assert h(p, 4, 256, 32, 8, p + 1, p, None) == -5
         assert h(p, 4, 256, 32, -2, p, p, None) == -3
         assert h(p, 4, 256, 300, 8, p, p, None) == -2
-        assert h(p, 4, 9000, 32, 8, p, p, None) == -4
+        assert h(p, 4, 70000, 32, 8, p, p, None) == -4
     for name in ("rtopk_rowwise_exact_f16", "rtopk_rowwise_exact_bf16"):
         h = getattr(lib, name)
-        assert h(p, 4, 9000, 32, p, p, None) == -4
+        assert h(p, 4, 70000, 32, p, p, None) == -4
         assert h(p, 4, 256, 0, p, p, None) == -2
 
 

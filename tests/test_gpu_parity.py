@@ -552,29 +552,27 @@ def test_nonfinite_inputs_terminate_and_stay_in_bounds_in_every_variant():
         ib, oi = guarded(N * k, torch.int32, -9)
         calls = [lambda: R.rtopk_rowwise_exact(xd, k, ov.view(N, k), oi.view(N, k)),
                  lambda: R.rtopk_rowwise(xd, k, 9, ov.view(N, k), oi.view(N, k))]
-        if M <= 8192:
-            calls += [lambda: R.rtopk_rowwise_exact_smallest(xd, k, ov.view(N, k), oi.view(N, k)),
-                      lambda: R.rtopk_rowwise_eps(xd, k, 1e-3, ov.view(N, k), oi.view(N, k))]
+        calls += [lambda: R.rtopk_rowwise_exact_smallest(xd, k, ov.view(N, k), oi.view(N, k)),
+                  lambda: R.rtopk_rowwise_eps(xd, k, 1e-3, ov.view(N, k), oi.view(N, k))]
         for call in calls:
             call()
             torch.cuda.synchronize()
             check(vb, 4321.0)
             check(ib, -9)
-        if M <= 8192:
-            db, od = guarded(N * M, torch.float32, 4321.0)
-            for mi in (-1, 7):
-                R.rtopk_maxk_dense(xd, k, mi, od.view(N, M))
-                torch.cuda.synchronize()
-                check(db, 4321.0)
-            for dt in (torch.float16, torch.bfloat16):
-                x16 = xd.to(dt)
-                hb, oh = guarded(N * k, dt, 7.0)
-                name = "f16" if dt == torch.float16 else "bf16"
-                getattr(R, f"rtopk_rowwise_exact_{name}")(x16, k, oh.view(N, k), oi.view(N, k))
-                getattr(R, f"rtopk_rowwise_{name}")(x16, k, 9, oh.view(N, k), oi.view(N, k))
-                torch.cuda.synchronize()
-                check(hb, 7.0)
-                check(ib, -9)
+        db, od = guarded(N * M, torch.float32, 4321.0)
+        for mi in (-1, 7):
+            R.rtopk_maxk_dense(xd, k, mi, od.view(N, M))
+            torch.cuda.synchronize()
+            check(db, 4321.0)
+        for dt in (torch.float16, torch.bfloat16):
+            x16 = xd.to(dt)
+            hb, oh = guarded(N * k, dt, 7.0)
+            name = "f16" if dt == torch.float16 else "bf16"
+            getattr(R, f"rtopk_rowwise_exact_{name}")(x16, k, oh.view(N, k), oi.view(N, k))
+            getattr(R, f"rtopk_rowwise_{name}")(x16, k, 9, oh.view(N, k), oi.view(N, k))
+            torch.cuda.synchronize()
+            check(hb, 7.0)
+            check(ib, -9)
 
 
 def test_hip_graph_replay_of_the_other_entry_points():
@@ -641,9 +639,7 @@ def test_randomised_shapes_modes_and_entry_points():
         else:
             x = workloads.laplace(N, M, seed)
         mi = int(rng.integers(0, 20))
-        kinds = ["exact", "early"]
-        if M <= 8192:
-            kinds += ["smallest_exact", "smallest_early", "eps", "dense_exact", "dense_early", "f16", "bf16"]
+        kinds = ["exact", "early", "smallest_exact", "smallest_early", "eps", "dense_exact", "dense_early", "f16", "bf16"]
         if M <= 256:
             kinds += ["u8_exact", "u8_early"]
         kind = kinds[rng.integers(len(kinds))]
@@ -701,3 +697,33 @@ def test_exit_iteration_statistics_of_table5_on_the_gpu():
                 assert 0.0 < paper - float(it.mean()) < 0.6, (M, k)
             else:
                 assert abs(float((it <= int(row[0])).mean() * 100.0) - paper) < 2.6, (M, k, row[0])
+
+
+@pytest.mark.parametrize("N,M,ks", [(5, 8196, (64, 4000)), (4, 9001, (33,)), (6, 16384, (1, 2048)), (3, 20000, (500,)),
+                                     (3, 32768, (4096,)), (3, 40001, (999,)), (4, 65536, (64, 65535, 65536))])
+def test_very_wide_rows_every_variant(N, M, ks):
+    # the k smallest, the precision-bounded mode, the dense form and 16-bit rows beyond 8192 columns
+    R = _gpu()
+    for x in (workloads.normal(N, M, seed=N * 5003 + M), workloads.normal_ties(N, M, seed=N * 5009 + M, p=0.5)):
+        xd = torch.from_numpy(x).cuda()
+        for k in ks:
+            tag = f"wide variants N={N} M={M} k={k}"
+            assert_smallest_parity(R, x, k, "exact", tag=tag)
+            assert_smallest_parity(R, x, k, "early", 7, tag=tag)
+            for eps in (0.0, 1e-4, 0.05):
+                assert_eps_parity(R, x, k, eps, tag=tag)
+            assert_dense_parity(R, x, k, -1, tag=tag, x_dev=xd)
+            assert_dense_parity(R, x, k, 6, tag=tag, x_dev=xd)
+            for kind in ("f16", "bf16"):
+                b = workloads.to_bits16(x, kind)
+                hd = torch.from_numpy(b.view(np.int16)).cuda().view(torch.float16 if kind == "f16" else torch.bfloat16)
+                for mode, mi in (("exact", 0), ("early", 6)):
+                    if mode == "exact":
+                        gv, gi = getattr(R, f"rtopk_rowwise_exact_{kind}")(hd, k)
+                        ov, oi = oracle.topk_exact_16(b, kind, k)
+                    else:
+                        gv, gi = getattr(R, f"rtopk_rowwise_{kind}")(hd, k, mi)
+                        ov, oi = oracle.topk_earlystop_16(b, kind, k, mi)
+                    torch.cuda.synchronize()
+                    assert np.array_equal(gi.cpu().numpy(), oi), f"{tag} {kind} {mode}"
+                    assert np.array_equal(gv.view(torch.int16).cpu().numpy().view(np.uint16), ov), f"{tag} {kind} {mode}"
