@@ -23,6 +23,13 @@
 
 #include "rtopk_kernel.hpp"
 
+// Share of a lane's E values counted per lane rather than by mask popcount (see count_ge_wide): all of
+// them here -- the few wavefronts that share a SIMD run in lock step between barriers, so nothing hides
+// the compare -> scalar popcount latency (8192 x 32768: 397 -> 380 us).
+#ifndef RTOPK_BLOCK_ACC_OF
+#define RTOPK_BLOCK_ACC_OF(E) (E)
+#endif
+
 namespace rtopk {
 
 // Inclusive prefix sum over the 64 lanes of a wavefront (not on the hot path: used once per row).
@@ -129,7 +136,7 @@ __global__ void __launch_bounds__(W * kWave)
   // cnt = #{row elements with key >= t}: this wavefront's share, then the sum over the workgroup.
   // `step` selects the half of s_cnt that is written; one barrier per step is enough because a half is
   // not written again before every wavefront has passed the next barrier.
-  constexpr int ACC = E <= 8 ? 0 : (E - 3) / 3;
+  constexpr int ACC = E <= 8 ? 0 : RTOPK_BLOCK_ACC_OF(E);
   int step = 0;
   auto count = [&](float t) -> int {
     const int mine = count_ge_wide<E, ACC, NEG>(x, t);

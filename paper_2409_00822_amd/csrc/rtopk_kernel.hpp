@@ -417,8 +417,13 @@ __device__ __forceinline__ void rows_max_and_min(const float (&x)[R][E], float (
   }
 }
 
+// How many of a wide row's E values per lane are counted per lane (v_cmp + v_addc, reduced once per
+// step) rather than by mask popcount on the scalar unit (see count_ge_wide).  From sweeps on MI355X:
+// a third up to 48 values per lane, two thirds at 64, all of them from 96 on -- the more registers a
+// wavefront holds the fewer wavefronts share a SIMD, and the less of the compare -> scalar popcount
+// latency is hidden (M = 8192: 361 -> 276 us per 32768 rows, M = 6144: 284 -> 239 us, M = 4096: 214 -> 205 us).
 #ifndef RTOPK_ACC_OF
-#define RTOPK_ACC_OF(E) (((E) - 3) / 3)
+#define RTOPK_ACC_OF(E) ((E) >= 96 ? (E) : ((E) >= 64 ? (2 * (E)) / 3 : ((E) - 3) / 3))
 #endif
 
 // Search and selection for one row held as xin[E] (lanes past column M hold duplicates of real
@@ -463,8 +468,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
 
   constexpr bool ASM = (E == 2 || E == 4 || E == 8);  // hand-scheduled loops exist for these widths
   constexpr bool KEEP = E <= 8;                       // masks of the last step stay in scalar registers
-  // wider rows: ACC of the E elements are counted per lane, which balances vector against scalar work
-  // (2*ACC + (E-ACC) + ~11 vector against 2*(E-ACC) + ~8 scalar instructions per step)
+  // wider rows: ACC of the E elements are counted per lane, the rest by mask popcount
   constexpr int ACC = KEEP ? 0 : RTOPK_ACC_OF(E);
   uint64_t m[KEEP ? E : 1];
   auto count = [&](float t) -> int {
