@@ -33,8 +33,8 @@ MEASURED_TRAFFIC = {
     ("c2_w512", 64, "f32", "pairs"): (2684434539, "profiles/rtopk_wave_kernel_c2_w512_k64.md"),
     ("c2_w1024", 128, "f32", "pairs"): (5368898628, "profiles/rtopk_wave_kernel_c2_w1024_k128.md"),
     ("c3_ties", 32, "f32", "pairs"): (2841766922, "profiles/rtopk_wave_kernel_c3_ties_k32.md"),
-    ("c4_wide", 64, "f32", "pairs"): (1107425398, "profiles/rtopk_wave_kernel_c4_wide_k64.md"),
-    ("x_wide32k", 256, "f32", "pairs"): (1090859314, "profiles/rtopk_block_kernel_x_wide32k_k256.md"),
+    ("c4_wide", 64, "f32", "pairs"): (1107427941, "profiles/rtopk_wave_kernel_c4_wide_k64.md"),
+    ("x_wide32k", 256, "f32", "pairs"): (1090836321, "profiles/rtopk_block_kernel_x_wide32k_k256.md"),
 }
 
 
@@ -237,17 +237,22 @@ def main():
         log(f"  parity {parity}, early-stop recall vs exact {recall:.4f}")
     if not args.no_cpu_baseline:
         log("timing the CPU oracle (exact mode) on the same input ...")
-        reps = []
-        for _ in range(9):
+
+        def oracle_pass():
             t0 = time.perf_counter()
             if half:
                 oracle.topk_exact_16(x_bits, args.dtype, k)
             else:
                 oracle.topk_exact(x_host, k)
-            reps.append(time.perf_counter() - t0)
-        t_cpu = statistics.median(reps[1:])
+            return time.perf_counter() - t0
+
+        first = oracle_pass()  # warm-up, also sizes the sample: about 10 s of CPU work in all
+        n_pass = int(min(100, max(8, round(10.0 / max(first, 1e-3)))))
+        reps = [oracle_pass() for _ in range(n_pass)]
+        t_cpu = statistics.median(reps)
         cpu = {"value": N / t_cpu, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"all {N} rows of the same input, exact mode (nth_element), median of 8 after 1 warm-up"}
+               "sample": f"all {N} rows of the same input, exact mode (nth_element per row, OpenMP over rows), "
+                         f"median of {n_pass} passes after 1 warm-up ({sum(reps):.1f} s of CPU work)"}
         log(f"  oracle: {t_cpu:.3f} s per pass on {cpu['cores']} threads")
 
     traffic = MEASURED_TRAFFIC.get((args.workload, k, args.dtype, args.op), (None, None)) if N == cfg["N"] else (None, None)
