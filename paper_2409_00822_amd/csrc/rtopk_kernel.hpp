@@ -570,7 +570,12 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
         if (cnt == k) break;
       }
     }
-    if (cnt < k) cnt = count(lo);  // the last step lowered hi (or none ran): the masks are not for lo
+    // The last step lowered hi (or none ran): the kept masks are not those of lo, so they are formed
+    // again.  Wide rows keep no masks and rank against lo directly; only when the last step counted
+    // exactly k can they skip the cut.
+    if constexpr (KEEP) {
+      if (cnt < k) cnt = count(lo);
+    }
     if (cnt == k) {
       emit_selection<G, NG, false, !KEEP, NEG, DENSE>(x, m, lo, lo, -1, lane, k, stage_addr, y);
     } else {
