@@ -13,6 +13,12 @@ static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
     if (u8) return hipErrorInvalidValue;
     return full ? launch<4, NG, R, true, kEarly, int32_t, true>(a) : launch<4, NG, R, false, kEarly, int32_t, true>(a);
   }
+  if constexpr (R > kRowsPerWaveFew) {
+    if (a.N < kFewRows) {
+      return full ? launch<4, NG, kRowsPerWaveFew, true, kEarly, int32_t>(a)
+                  : launch<4, NG, kRowsPerWaveFew, false, kEarly, int32_t>(a);
+    }
+  }
   return full ? launch<4, NG, R, true, kEarly, int32_t>(a) : launch<4, NG, R, false, kEarly, int32_t>(a);
 }
 

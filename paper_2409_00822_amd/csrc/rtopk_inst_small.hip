@@ -16,6 +16,12 @@ static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
       return full ? launch<G, NG, R, true, MODE, int32_t, true>(a) : launch<G, NG, R, false, MODE, int32_t, true>(a);
     }
   }
+  if constexpr (R > kRowsPerWaveFew && G == 2) {
+    if (a.N < kFewRows) {
+      return full ? launch<G, NG, kRowsPerWaveFew, true, MODE, int32_t>(a)
+                  : launch<G, NG, kRowsPerWaveFew, false, MODE, int32_t>(a);
+    }
+  }
   return full ? launch<G, NG, R, true, MODE, int32_t>(a) : launch<G, NG, R, false, MODE, int32_t>(a);
 }
 

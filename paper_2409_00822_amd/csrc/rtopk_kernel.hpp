@@ -869,4 +869,11 @@ hipError_t launch(const LaunchArgs& a) {
 // 8 for M = 256, 2 for M = 512..1024 (M = 512 runs 10 % slower with 4), 1 beyond.
 constexpr int rows_per_wave(int E) { return E <= 2 ? 16 : (E <= 4 ? 8 : (E <= 16 ? 2 : 1)); }
 
+// Few rows: with 8 or 16 rows per wavefront a launch of less than ~32768 rows does not even put two
+// wavefronts on every SIMD, and each of them walks its rows one after the other.  Two rows per wavefront
+// then spread the same work over more wavefronts (M = 256: 4096 rows 10.5 -> 6.6 us, 16384 rows
+// 11.8 -> 9.4 us; no difference from 65536 rows on).
+constexpr int64_t kFewRows = 32768;
+constexpr int kRowsPerWaveFew = 2;
+
 }  // namespace rtopk

@@ -727,3 +727,15 @@ def test_very_wide_rows_every_variant(N, M, ks):
                     torch.cuda.synchronize()
                     assert np.array_equal(gi.cpu().numpy(), oi), f"{tag} {kind} {mode}"
                     assert np.array_equal(gv.view(torch.int16).cpu().numpy().view(np.uint16), ov), f"{tag} {kind} {mode}"
+
+
+@pytest.mark.parametrize("N,M,k", [(32768 + 5, 256, 32), (32768 + 13, 128, 16), (32768 + 3, 200, 25), (40001, 64, 8)])
+def test_many_rows_with_a_ragged_last_wavefront(N, M, k):
+    # from 32768 rows on, narrow rows go 8 or 16 to a wavefront; the last wavefront holds fewer
+    R = _gpu()
+    x = workloads.normal_ties(N, M, seed=N + M, p=0.1)
+    assert_parity(R, x, k, "exact", tag=f"N={N} M={M}")
+    assert_parity(R, x, k, "early", 6, tag=f"N={N} M={M}")
+    assert_parity(R, x, k, "exact", u8=True, tag=f"u8 N={N} M={M}")
+    assert_dense_parity(R, x, k, -1, tag=f"dense N={N} M={M}")
+    assert_smallest_parity(R, x, k, "exact", tag=f"smallest N={N} M={M}")
