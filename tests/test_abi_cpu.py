@@ -110,3 +110,17 @@ def test_binding_refuses_host_tensors():
 
     with pytest.raises(ValueError):
         R.rtopk_rowwise_exact(torch.zeros(4, 8), 2)
+
+
+def test_generated_search_loops_are_current():
+    # rtopk_search_loops.inc is committed so that a plain hipcc build needs no Python; it must be what
+    # the generator writes today
+    import importlib.util
+
+    csrc = os.path.join(ROOT, "paper_2409_00822_amd", "csrc")
+    spec = importlib.util.spec_from_file_location("gen_search_loops", os.path.join(csrc, "gen_search_loops.py"))
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    committed = open(os.path.join(csrc, "rtopk_search_loops.inc")).read()
+    gen.main()  # rewrites the file only if it differs
+    assert open(os.path.join(csrc, "rtopk_search_loops.inc")).read() == committed
