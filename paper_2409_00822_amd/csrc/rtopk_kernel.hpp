@@ -426,6 +426,66 @@ __device__ __forceinline__ void rows_max_and_min(const float (&x)[R][E], float (
   }
 }
 
+// In the lanes whose bit is set in `mask`: LDS[addr] = v (EXEC restored to all ones, as above).
+__device__ __forceinline__ void lds_store_masked(uint64_t mask, uint32_t addr, float v) {
+  asm volatile(
+      "s_mov_b64 exec, %0\n\t"
+      "ds_write_b32 %1, %2\n\t"
+      "s_mov_b64 exec, -1"
+      :
+      : "s"(mask), "v"(addr), "v"(v)
+      : "memory");
+}
+
+// Narrowing of a wide row's search.  A threshold between lo and hi separates only the elements whose
+// key lies in [lo, hi); everything at or above hi is counted by every later threshold and everything
+// below lo by none.  On the rows this method is meant for that band empties fast -- the bisection is
+// over the value range, and after three to five steps it holds a few hundred of thousands of elements
+// (median 161 of 4096 after three steps and 68 after four on Laplace rows, 277 of 8192 after four on
+// normal ones) -- so once at most kBandRegs*64 elements are left they are gathered, in any order, into
+// kBandRegs registers per lane and the remaining steps compare those instead of the whole row:
+//   #{key >= t} = #{key >= hi} + #{band members with key >= t}    for every lo <= t < hi.
+// Thresholds, counts and therefore the result are exactly those of the full-width search.
+constexpr int kBandRegs = 4;
+
+// Gathers the row's band members through `scratch` (kBandRegs*64 floats of LDS) into y[]; lanes beyond
+// the band hold a key of -inf.  Returns #{key >= hi}.  The caller guarantees the band fits.
+template <int E, bool NEG>
+__device__ __forceinline__ int gather_band(const float (&x)[E], float lo, float hi, int lane, uint32_t scratch,
+                                           float (&y)[kBandRegs]) {
+  int above = 0;
+  uint32_t nb = 0;  // wave-uniform: band members found so far
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const float key = keyof<NEG>(x[e]);
+    const uint64_t a = __builtin_amdgcn_ballot_w64(key >= hi);
+    const uint64_t b = __builtin_amdgcn_ballot_w64(key >= lo) & ~a;
+    above += __builtin_popcountll(a);
+    lds_store_masked(b, scratch + lanes_below(b, nb) * 4u, x[e]);
+    nb += (uint32_t)__builtin_popcountll(b);
+    if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // keep the masks of later elements from piling up
+  }
+  // The LDS queue of a wavefront is served in order, so the reads below see the writes above; the
+  // wait is written out because the compiler does not track LDS operations inside asm blocks.
+  static_assert(kBandRegs == 4, "the gather reads four values per lane");
+  float v0, v1, v2, v3;
+  asm volatile(
+      "ds_read_b32 %0, %4\n\t"
+      "ds_read_b32 %1, %4 offset:256\n\t"
+      "ds_read_b32 %2, %4 offset:512\n\t"
+      "ds_read_b32 %3, %4 offset:768\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "v"(scratch + (uint32_t)lane * 4u)
+      : "memory");
+  const float none = NEG ? __builtin_inff() : -__builtin_inff();
+  y[0] = (uint32_t)lane < nb ? v0 : none;
+  y[1] = (uint32_t)lane + 64u < nb ? v1 : none;
+  y[2] = (uint32_t)lane + 128u < nb ? v2 : none;
+  y[3] = (uint32_t)lane + 192u < nb ? v3 : none;
+  return above;
+}
+
 // How many of a wide row's E values per lane are counted per lane (v_cmp + v_addc, reduced once per
 // step) rather than by mask popcount on the scalar unit (see count_ge_wide).  From sweeps on MI355X:
 // a third up to 48 values per lane, two thirds at 64, all of them from 96 on -- the more registers a
@@ -497,6 +557,11 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     if constexpr (ASM) {
       hit = search_exact_asm(x, lo, hi, k, m, std::integral_constant<bool, NEG>(), std::integral_constant<int, DT>());
     } else {
+      // cnt_lo = #{key >= lo} and a lower bound cnt_hi of #{key >= hi} bound the band [lo, hi) from
+      // above; once it fits kBandRegs registers per lane the search narrows to it (see gather_band).
+      constexpr bool NARROW = E >= 32;
+      int cnt_lo = M, cnt_hi = 0;
+      bool narrow = false;
       float seen = lo;
       for (;;) {
         thres = midpoint_exact<DT>(lo, hi);
@@ -508,6 +573,14 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
           break;
         }
         move_bound(lo, hi, thres, cnt, k);
+        if constexpr (NARROW) {
+          cnt_lo = cnt < k ? cnt_lo : cnt;
+          cnt_hi = cnt < k ? cnt : cnt_hi;
+          if (cnt_lo - cnt_hi <= kBandRegs * kWave) {
+            narrow = true;
+            break;
+          }
+        }
         thres = midpoint_exact<DT>(lo, hi);
         cnt = count(thres);
         if (cnt == k) {
@@ -515,6 +588,36 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
           break;
         }
         move_bound(lo, hi, thres, cnt, k);
+        if constexpr (NARROW) {
+          cnt_lo = cnt < k ? cnt_lo : cnt;
+          cnt_hi = cnt < k ? cnt : cnt_hi;
+          if (cnt_lo - cnt_hi <= kBandRegs * kWave) {
+            narrow = true;
+            break;
+          }
+        }
+      }
+      if constexpr (NARROW) {
+        if (narrow) {
+          float band[kBandRegs];
+          const int above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band);
+          for (;;) {
+            // converged when the midpoint is not strictly inside (lo, hi): the same state the test
+            // against the previous midpoint above detects, one or two steps earlier
+            const float mid = midpoint_exact<DT>(lo, hi);
+            if (!(mid > lo && mid < hi)) break;
+            thres = mid;
+            int cnt = above;
+#pragma unroll
+            for (int j = 0; j < kBandRegs; ++j)
+              cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keyof<NEG>(band[j]) >= thres));
+            if (cnt == k) {
+              hit = true;
+              break;
+            }
+            move_bound(lo, hi, thres, cnt, k);
+          }
+        }
       }
     }
     if (hit) {
@@ -698,7 +801,10 @@ __global__ void __launch_bounds__(256)
   const int64_t r0 = ((int64_t)blockIdx.x * waves_per_block + wave) * R;
   if (r0 >= N) return;
   const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
-  uint2* stage = stage_all + (size_t)wave * R * k;
+  // per wavefront: R*k pairs, and at least the band scratch where the exact search of a wide row uses it
+  constexpr int kMinPairs = (E >= 32 && MODE == kExact) ? kBandRegs * kWave / 2 : 0;
+  const int pairs_per_wave = R * k > kMinPairs ? R * k : kMinPairs;
+  uint2* stage = stage_all + (size_t)wave * pairs_per_wave;
 
   // Loading stage: all R rows' loads are issued before any is consumed.
   float x[R][E];
@@ -797,12 +903,14 @@ template <int G, int NG, int R, bool FULL, int MODE>
 __global__ void __launch_bounds__(256)
     rtopk_dense_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter, float* __restrict__ out) {
   constexpr int E = G * NG;
+  extern __shared__ uint2 band_scratch[];  // [waves per block][kBandRegs * 64 floats], wide rows in exact mode only
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int waves_per_block = (int)(blockDim.x >> 6);
   const int64_t r0 = ((int64_t)blockIdx.x * waves_per_block + wave) * R;
   if (r0 >= N) return;
   const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
+  uint2* scratch = band_scratch + (size_t)wave * (kBandRegs * kWave / 2);
 
   float x[R][E];
 #pragma unroll
@@ -824,7 +932,7 @@ __global__ void __launch_bounds__(256)
   for (int rr = 0; rr < R; ++rr) {
     if (rr < nrows) {
       float y[E];
-      select_row<G, NG, FULL, MODE, false, kF32, true>(x[rr], lane, M, k, max_iter, 0.0f, nullptr, y, row_max[rr],
+      select_row<G, NG, FULL, MODE, false, kF32, true>(x[rr], lane, M, k, max_iter, 0.0f, scratch, y, row_max[rr],
                                                        row_min[rr]);
       float* orow = out + (r0 + rr) * (int64_t)M;
 #pragma unroll
@@ -842,7 +950,8 @@ hipError_t launch_dense(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((rtopk_dense_kernel<G, NG, R, FULL, MODE>), dim3((unsigned)blocks), dim3(waves * kWave), 0,
+  const size_t lds = (G * NG >= 32 && MODE == kExact) ? (size_t)waves * kBandRegs * kWave * sizeof(float) : 0;
+  hipLaunchKernelGGL((rtopk_dense_kernel<G, NG, R, FULL, MODE>), dim3((unsigned)blocks), dim3(waves * kWave), lds,
                      a.stream, static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter,
                      static_cast<float*>(a.out_vals));
   return hipGetLastError();
@@ -853,7 +962,9 @@ hipError_t launch_dense(const LaunchArgs& a) {
 template <int G, int NG, int R, bool FULL, int MODE, typename IdxT, bool NEG = false, int DT = kF32>
 hipError_t launch(const LaunchArgs& a) {
   // LDS per wavefront: R*k staged pairs of 8 bytes; at most 64 KiB per block.
-  const size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
+  size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
+  // the exact search of wide rows gathers its band through the (not yet used) staging area
+  if (G * NG >= 32 && MODE == kExact && per_wave < kBandRegs * kWave * sizeof(float)) per_wave = kBandRegs * kWave * sizeof(float);
   int waves = RTOPK_WAVES_PER_BLOCK;
   while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
   const int64_t batches = (a.N + R - 1) / R;
