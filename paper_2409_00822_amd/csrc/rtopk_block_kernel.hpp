@@ -81,6 +81,13 @@ __global__ void __launch_bounds__(W * kWave)
   __shared__ float s_hi[W], s_nlo[W];  // per-wavefront maximum and negated minimum
   __shared__ int s_cnt[2][W];          // per-wavefront counts of a search step, double buffered
   __shared__ int s_tab[2][T];          // candidates per cell of class A / class B, then their exclusive prefixes
+  // narrowing of Algorithm 1's search (see gather_band): per-wavefront gather areas, the whole row's
+  // band, its per-wavefront sizes, and what wavefront 0 hands back after finishing the search alone
+  __shared__ float s_gather[W][kBandRegs * kWave];
+  __shared__ float s_band[kBandRegs * kWave];
+  __shared__ int s_nb[W], s_above[W];
+  __shared__ float s_res[3];
+  __shared__ int s_resi[2];
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -153,9 +160,19 @@ __global__ void __launch_bounds__(W * kWave)
   float tA, tB = 0.0f;
   int limA = k, limB = 0;
   if constexpr (MODE == kExact || MODE == kEps) {
-    // Algorithm 1; termination, collection and iteration numbering as in select_row.
-    bool hit = false;
+    // Algorithm 1; termination, collection and iteration numbering as in select_row.  The full-width
+    // steps track cnt_lo = #{key >= lo} and a lower bound cnt_hi of #{key >= hi}; once the band
+    // [lo, hi) of the whole row fits kBandRegs registers per lane of ONE wavefront, it is gathered
+    // there and wavefront 0 finishes the search alone, with no further barriers.
+    bool hit = false, narrow = false;
     float thres = lo;
+    int steps = 0, cnt_lo = M, cnt_hi = 0;
+    const float eps = MODE == kEps ? eps_rel * __builtin_fabsf(hi) : 0.0f;
+    auto fits = [&](int cnt) -> bool {  // after move_bound with this count
+      cnt_lo = cnt < k ? cnt_lo : cnt;
+      cnt_hi = cnt < k ? cnt : cnt_hi;
+      return cnt_lo - cnt_hi <= kBandRegs * kWave;
+    };
     if constexpr (MODE == kExact) {
       float seen = lo;
       for (;;) {
@@ -168,6 +185,10 @@ __global__ void __launch_bounds__(W * kWave)
           break;
         }
         move_bound(lo, hi, thres, cnt, k);
+        if (fits(cnt)) {
+          narrow = true;
+          break;
+        }
         thres = midpoint_exact<DT>(lo, hi);
         cnt = count(thres);
         if (cnt == k) {
@@ -175,10 +196,12 @@ __global__ void __launch_bounds__(W * kWave)
           break;
         }
         move_bound(lo, hi, thres, cnt, k);
+        if (fits(cnt)) {
+          narrow = true;
+          break;
+        }
       }
     } else {
-      const float eps = eps_rel * __builtin_fabsf(hi);
-      int steps = 0;
       while (hi - lo > eps) {
         const float mid = (lo + hi) * 0.5f;
         if (!(mid > lo && mid < hi)) break;
@@ -190,7 +213,58 @@ __global__ void __launch_bounds__(W * kWave)
           break;
         }
         move_bound(lo, hi, thres, cnt, k);
+        if (fits(cnt)) {
+          narrow = true;
+          break;
+        }
       }
+    }
+    if (narrow) {  // uniform over the workgroup
+      // every wavefront gathers its own band members, then appends them to the row's band
+      float band[kBandRegs];
+      uint32_t nb;
+      const int above = gather_band<E, NEG, true>(x, lo, hi, lane, (uint32_t)(uintptr_t)s_gather[wave], band, nb);
+      if (lane == 0) {
+        s_nb[wave] = (int)nb;
+        s_above[wave] = above;
+      }
+      __syncthreads();
+      uint32_t off = 0, total = 0;
+      int above_all = 0;
+#pragma unroll
+      for (int w = 0; w < W; ++w) {
+        const uint32_t n = (uint32_t)s_nb[w];
+        off += w < wave ? n : 0u;
+        total += n;
+        above_all += s_above[w];
+      }
+      const uint32_t dst = (uint32_t)(uintptr_t)s_band;
+#pragma unroll
+      for (int j = 0; j < kBandRegs; ++j) {
+        const uint32_t i = (uint32_t)lane + 64u * j;
+        lds_store_masked(__builtin_amdgcn_ballot_w64(i < nb), dst + (off + i) * 4u, band[j]);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        float all[kBandRegs];
+        load_band<NEG>(dst, lane, total, all);
+        search_band<MODE, NEG, DT>(all, above_all, k, eps, lo, hi, thres, hit, steps);
+        if (lane == 0) {
+          s_res[0] = lo;
+          s_res[1] = hi;
+          s_res[2] = thres;
+          s_resi[0] = hit ? 1 : 0;
+          s_resi[1] = steps;
+        }
+      }
+      __syncthreads();
+      lo = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_res[0])));
+      hi = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_res[1])));
+      thres = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_res[2])));
+      hit = __builtin_amdgcn_readfirstlane(s_resi[0]) != 0;
+      steps = __builtin_amdgcn_readfirstlane(s_resi[1]);
+    }
+    if constexpr (MODE == kEps) {
       if (out_iters != nullptr && threadIdx.x == 0) out_iters[r] = hit ? steps : steps + 1;
     }
     if (hit) {

@@ -426,6 +426,18 @@ __device__ __forceinline__ void rows_max_and_min(const float (&x)[R][E], float (
   }
 }
 
+// Exact mode on rows stored in 16 bits: the midpoint with the fp32 bits below the row type's precision
+// cleared (see gen_search_loops.py for why this ends the search early and is still exact).
+template <int DT>
+__device__ __forceinline__ float midpoint_exact(float lo, float hi) {
+  const float t = (lo + hi) * 0.5f;
+  if constexpr (DT == kF32) {
+    return t;
+  } else {
+    return __uint_as_float(__float_as_uint(t) & (DT == kBF16 ? 0xffff0000u : 0xffffe000u));
+  }
+}
+
 // In the lanes whose bit is set in `mask`: LDS[addr] = v (EXEC restored to all ones, as above).
 __device__ __forceinline__ void lds_store_masked(uint64_t mask, uint32_t addr, float v) {
   asm volatile(
@@ -447,27 +459,16 @@ __device__ __forceinline__ void lds_store_masked(uint64_t mask, uint32_t addr, f
 //   #{key >= t} = #{key >= hi} + #{band members with key >= t}    for every lo <= t < hi.
 // Thresholds, counts and therefore the result are exactly those of the full-width search.
 constexpr int kBandRegs = 4;
+// Which kernels narrow: Algorithm 1 (exact or precision-bounded) on rows of 24 or more values per lane,
+// which are the widths that go one row to a wavefront, so that the row's staging area is still unused.
+constexpr bool narrows(int E, int mode) { return E >= 24 && (mode == kExact || mode == kEps); }
 
-// Gathers the row's band members through `scratch` (kBandRegs*64 floats of LDS) into y[]; lanes beyond
-// the band hold a key of -inf.  Returns #{key >= hi}.  The caller guarantees the band fits.
-template <int E, bool NEG>
-__device__ __forceinline__ int gather_band(const float (&x)[E], float lo, float hi, int lane, uint32_t scratch,
-                                           float (&y)[kBandRegs]) {
-  int above = 0;
-  uint32_t nb = 0;  // wave-uniform: band members found so far
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const float key = keyof<NEG>(x[e]);
-    const uint64_t a = __builtin_amdgcn_ballot_w64(key >= hi);
-    const uint64_t b = __builtin_amdgcn_ballot_w64(key >= lo) & ~a;
-    above += __builtin_popcountll(a);
-    lds_store_masked(b, scratch + lanes_below(b, nb) * 4u, x[e]);
-    nb += (uint32_t)__builtin_popcountll(b);
-    if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // keep the masks of later elements from piling up
-  }
-  // The LDS queue of a wavefront is served in order, so the reads below see the writes above; the
-  // wait is written out because the compiler does not track LDS operations inside asm blocks.
-  static_assert(kBandRegs == 4, "the gather reads four values per lane");
+// y[j] = the (lane + 64 j)-th of the nb floats at LDS address `scratch`, or a key of -inf beyond them.
+// The LDS queue of a wavefront is served in order, so the reads see the wavefront's earlier writes; the
+// wait is written out because the compiler does not track LDS operations inside asm blocks.
+template <bool NEG>
+__device__ __forceinline__ void load_band(uint32_t scratch, int lane, uint32_t nb, float (&y)[kBandRegs]) {
+  static_assert(kBandRegs == 4, "four values per lane");
   float v0, v1, v2, v3;
   asm volatile(
       "ds_read_b32 %0, %4\n\t"
@@ -483,7 +484,64 @@ __device__ __forceinline__ int gather_band(const float (&x)[E], float lo, float 
   y[1] = (uint32_t)lane + 64u < nb ? v1 : none;
   y[2] = (uint32_t)lane + 128u < nb ? v2 : none;
   y[3] = (uint32_t)lane + 192u < nb ? v3 : none;
+}
+
+// Gathers the row's band members through `scratch` (kBandRegs*64 floats of LDS) into y[]; lanes beyond
+// the band hold a key of -inf.  Returns #{key >= hi}.  The caller guarantees the band fits.
+// SPARSE: most of the lane masks are expected to be empty (a workgroup's band is spread over all its
+// wavefronts), so each is tested before it is ranked and stored.
+template <int E, bool NEG, bool SPARSE = false>
+__device__ __forceinline__ int gather_band(const float (&x)[E], float lo, float hi, int lane, uint32_t scratch,
+                                           float (&y)[kBandRegs], uint32_t& nb) {
+  int above = 0;
+  nb = 0;  // wave-uniform: band members found so far
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const float key = keyof<NEG>(x[e]);
+    const uint64_t a = __builtin_amdgcn_ballot_w64(key >= hi);
+    const uint64_t b = __builtin_amdgcn_ballot_w64(key >= lo) & ~a;
+    above += __builtin_popcountll(a);
+    if (!SPARSE || b != 0) {
+      lds_store_masked(b, scratch + lanes_below(b, nb) * 4u, x[e]);
+      nb += (uint32_t)__builtin_popcountll(b);
+    }
+    if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // keep the masks of later elements from piling up
+  }
+  load_band<NEG>(scratch, lane, nb, y);
   return above;
+}
+
+// #{band members with key >= t}
+template <bool NEG>
+__device__ __forceinline__ int count_band(const float (&band)[kBandRegs], float t) {
+  int cnt = 0;
+#pragma unroll
+  for (int j = 0; j < kBandRegs; ++j) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keyof<NEG>(band[j]) >= t));
+  return cnt;
+}
+
+// The rest of Algorithm 1's loop on a gathered band (`above` = #{key >= hi} when it was gathered):
+// exact mode until a step counts k or the midpoint is no longer strictly inside (lo, hi) -- the state
+// the full-width loop detects, one or two steps later, by its midpoint repeating -- and the
+// precision-bounded mode with its own guard and step count.
+template <int MODE, bool NEG, int DT>
+__device__ __forceinline__ void search_band(const float (&band)[kBandRegs], int above, int k, float eps, float& lo,
+                                            float& hi, float& thres, bool& hit, int& steps) {
+  for (;;) {
+    if constexpr (MODE == kEps) {
+      if (!(hi - lo > eps)) break;
+    }
+    const float mid = MODE == kEps ? (lo + hi) * 0.5f : midpoint_exact<DT>(lo, hi);
+    if (!(mid > lo && mid < hi)) break;
+    thres = mid;
+    ++steps;
+    const int cnt = above + count_band<NEG>(band, thres);
+    if (cnt == k) {
+      hit = true;
+      break;
+    }
+    move_bound(lo, hi, thres, cnt, k);
+  }
 }
 
 // How many of a wide row's E values per lane are counted per lane (v_cmp + v_addc, reduced once per
@@ -501,18 +559,6 @@ __device__ __forceinline__ int gather_band(const float (&x)[E], float lo, float 
 //         kEps = Algorithm 1 with epsilon = eps_rel * |max|.
 // Returns the exit iteration of the search loop (kEps only; 0 otherwise): the number of midpoints
 // evaluated when one of them counted exactly k, one more when the loop ended through its guard.
-// Exact mode on rows stored in 16 bits: the midpoint with the fp32 bits below the row type's precision
-// cleared (see gen_search_loops.py for why this ends the search early and is still exact).
-template <int DT>
-__device__ __forceinline__ float midpoint_exact(float lo, float hi) {
-  const float t = (lo + hi) * 0.5f;
-  if constexpr (DT == kF32) {
-    return t;
-  } else {
-    return __uint_as_float(__float_as_uint(t) & (DT == kBF16 ? 0xffff0000u : 0xffffe000u));
-  }
-}
-
 //   DENSE: the result is y[] (chosen values in place, +0 elsewhere) instead of pairs staged at `stage`.
 //   row_max, row_min: the row's maximum and minimum (Alg. 1 / Alg. 2, first two steps), wave-uniform.
 template <int G, int NG, bool FULL, int MODE, bool NEG, int DT = kF32, bool DENSE = false>
@@ -559,7 +605,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     } else {
       // cnt_lo = #{key >= lo} and a lower bound cnt_hi of #{key >= hi} bound the band [lo, hi) from
       // above; once it fits kBandRegs registers per lane the search narrows to it (see gather_band).
-      constexpr bool NARROW = E >= 32;
+      constexpr bool NARROW = narrows(E, MODE);
       int cnt_lo = M, cnt_hi = 0;
       bool narrow = false;
       float seen = lo;
@@ -600,23 +646,10 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       if constexpr (NARROW) {
         if (narrow) {
           float band[kBandRegs];
-          const int above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band);
-          for (;;) {
-            // converged when the midpoint is not strictly inside (lo, hi): the same state the test
-            // against the previous midpoint above detects, one or two steps earlier
-            const float mid = midpoint_exact<DT>(lo, hi);
-            if (!(mid > lo && mid < hi)) break;
-            thres = mid;
-            int cnt = above;
-#pragma unroll
-            for (int j = 0; j < kBandRegs; ++j)
-              cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keyof<NEG>(band[j]) >= thres));
-            if (cnt == k) {
-              hit = true;
-              break;
-            }
-            move_bound(lo, hi, thres, cnt, k);
-          }
+          uint32_t nb;
+          const int above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band, nb);
+          int unused_steps = 0;
+          search_band<kExact, NEG, DT>(band, above, k, 0.0f, lo, hi, thres, hit, unused_steps);
         }
       }
     }
@@ -639,17 +672,38 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     bool hit = false;
     float thres = lo;
     int steps = 0;
+    // narrowing as in the exact mode: same thresholds and counts, hence the same exit iteration
+    constexpr bool NARROW = narrows(E, MODE);
+    int cnt_lo = M, cnt_hi = 0, above = 0;
+    bool narrow = false;
+    float band[kBandRegs];
     while (hi - lo > eps) {
       const float mid = (lo + hi) * 0.5f;
       if (!(mid > lo && mid < hi)) break;
       thres = mid;
       ++steps;
-      const int cnt = count(thres);
+      int cnt;
+      if (NARROW && narrow) {
+        cnt = above + count_band<NEG>(band, thres);
+      } else {
+        cnt = count(thres);
+      }
       if (cnt == k) {
         hit = true;
         break;
       }
       move_bound(lo, hi, thres, cnt, k);
+      if constexpr (NARROW) {
+        if (!narrow) {
+          cnt_lo = cnt < k ? cnt_lo : cnt;
+          cnt_hi = cnt < k ? cnt : cnt_hi;
+          if (cnt_lo - cnt_hi <= kBandRegs * kWave) {
+            uint32_t nb;
+            above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band, nb);
+            narrow = true;
+          }
+        }
+      }
     }
     if (hit) {
       emit_selection<G, NG, false, !KEEP, NEG, DENSE>(x, m, thres, thres, -1, lane, k, stage_addr, y);
@@ -802,7 +856,8 @@ __global__ void __launch_bounds__(256)
   if (r0 >= N) return;
   const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
   // per wavefront: R*k pairs, and at least the band scratch where the exact search of a wide row uses it
-  constexpr int kMinPairs = (E >= 32 && MODE == kExact) ? kBandRegs * kWave / 2 : 0;
+  static_assert(!narrows(E, MODE) || R == 1, "the band scratch reuses the staging area of the wavefront's only row");
+  constexpr int kMinPairs = narrows(E, MODE) ? kBandRegs * kWave / 2 : 0;
   const int pairs_per_wave = R * k > kMinPairs ? R * k : kMinPairs;
   uint2* stage = stage_all + (size_t)wave * pairs_per_wave;
 
@@ -950,7 +1005,7 @@ hipError_t launch_dense(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  const size_t lds = (G * NG >= 32 && MODE == kExact) ? (size_t)waves * kBandRegs * kWave * sizeof(float) : 0;
+  const size_t lds = narrows(G * NG, MODE) ? (size_t)waves * kBandRegs * kWave * sizeof(float) : 0;
   hipLaunchKernelGGL((rtopk_dense_kernel<G, NG, R, FULL, MODE>), dim3((unsigned)blocks), dim3(waves * kWave), lds,
                      a.stream, static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter,
                      static_cast<float*>(a.out_vals));
@@ -964,8 +1019,11 @@ hipError_t launch(const LaunchArgs& a) {
   // LDS per wavefront: R*k staged pairs of 8 bytes; at most 64 KiB per block.
   size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
   // the exact search of wide rows gathers its band through the (not yet used) staging area
-  if (G * NG >= 32 && MODE == kExact && per_wave < kBandRegs * kWave * sizeof(float)) per_wave = kBandRegs * kWave * sizeof(float);
-  int waves = RTOPK_WAVES_PER_BLOCK;
+  if (narrows(G * NG, MODE) && per_wave < kBandRegs * kWave * sizeof(float)) per_wave = kBandRegs * kWave * sizeof(float);
+  // one wavefront per workgroup, except where a wavefront stages 8 KiB or more of pairs: there four
+  // per workgroup measured 7 % faster (2^20 x 256, k = 128: 387 -> 360 us), while at 4 KiB and below
+  // one per workgroup is the faster by 3-11 %
+  int waves = per_wave >= 8192 ? 4 : RTOPK_WAVES_PER_BLOCK;
   while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
