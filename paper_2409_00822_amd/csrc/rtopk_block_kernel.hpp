@@ -356,7 +356,8 @@ __global__ void __launch_bounds__(W * kWave)
           const uint32_t fb = __float_as_uint(x[g * G + c]);
           uint32_t bits = fb;
           if constexpr (DT != kF32) bits = narrow_bits<DT>(fb);
-          store_pair_masked<DT>(mk, ov, pos * (uint32_t)sizeof(OutT), bits, oi, pos * 4u, col0 + c);
+          // most masks are empty when k is a small part of the row: skip their store instructions
+          if (mk != 0) store_pair_masked<DT>(mk, ov, pos * (uint32_t)sizeof(OutT), bits, oi, pos * 4u, col0 + c);
         }
         if (c + 1 < G) pos = add_mask_bit(pos, m[c]);
       }
