@@ -459,9 +459,9 @@ __device__ __forceinline__ void lds_store_masked(uint64_t mask, uint32_t addr, f
 //   #{key >= t} = #{key >= hi} + #{band members with key >= t}    for every lo <= t < hi.
 // Thresholds, counts and therefore the result are exactly those of the full-width search.
 constexpr int kBandRegs = 4;
-// Which kernels narrow: Algorithm 1 (exact or precision-bounded) on rows of 24 or more values per lane,
-// which are the widths that go one row to a wavefront, so that the row's staging area is still unused.
-constexpr bool narrows(int E, int mode) { return E >= 24 && (mode == kExact || mode == kEps); }
+// Which kernels narrow: those for rows of 24 or more values per lane, which are the widths that go one
+// row to a wavefront, so that the row's staging area is still unused while it is searched.
+constexpr bool narrows(int E, int /*mode*/) { return E >= 24; }
 
 // y[j] = the (lane + 64 j)-th of the nb floats at LDS address `scratch`, or a key of -inf beyond them.
 // The LDS queue of a wavefront is served in order, so the reads see the wavefront's earlier writes; the
@@ -718,13 +718,34 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     if constexpr (ASM) {
       cnt = search_early_asm(x, lo, hi, k, max_iter, m, std::integral_constant<bool, NEG>());
     } else {
+      // narrowing as in Algorithm 1: every midpoint lies in [lo, hi], so the identity behind it holds
+      constexpr bool NARROW = narrows(E, MODE);
+      int cnt_lo = M, cnt_hi = 0, above = 0;
+      bool narrow = false;
+      float band[kBandRegs];
       for (int it = 0; it < max_iter; ++it) {
         const float thres = (lo + hi) * 0.5f;
-        cnt = count(thres);
+        if (NARROW && narrow) {
+          cnt = above + count_band<NEG>(band, thres);
+        } else {
+          cnt = count(thres);
+        }
         // cnt == k: from here on lo can only move to thresholds that still count exactly k, so the
         // selection is already final.
         move_bound(lo, hi, thres, cnt, k);
         if (cnt == k) break;
+        if constexpr (NARROW) {
+          if (!narrow) {
+            cnt_lo = cnt < k ? cnt_lo : cnt;
+            cnt_hi = cnt < k ? cnt : cnt_hi;
+            // the gather costs about as much as three full-width steps: only when more remain
+            if (cnt_lo - cnt_hi <= kBandRegs * kWave && it + 6 < max_iter) {
+              uint32_t nb;
+              above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band, nb);
+              narrow = true;
+            }
+          }
+        }
       }
     }
     // The last step lowered hi (or none ran): the kept masks are not those of lo, so they are formed
