@@ -26,15 +26,15 @@ PEAK_HBM_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # size), from the rocprofv3 --pmc runs summarised under profiles/ (not measured live: counters need the
 # profiler).  Keyed by (workload, k, dtype, op) at the workload's full row count.
 MEASURED_TRAFFIC = {
-    ("c1_maxk", 32, "f32", "pairs"): (1342397423, "profiles/rtopk_wave_kernel_c1_maxk_k32.md"),
-    ("c1_maxk", 32, "bf16", "pairs"): (738381980, "profiles/rtopk_wave_kernel_c1_maxk_k32dtypebf16.md"),
-    ("c1_maxk", 32, "f32", "dense"): (2147638658, "profiles/rtopk_dense_kernel_c1_maxk_k32opdense.md"),
-    ("c2_w128", 16, "f32", "pairs"): (671338619, "profiles/rtopk_wave_kernel_c2_w128_k16.md"),
-    ("c2_w512", 64, "f32", "pairs"): (2684437179, "profiles/rtopk_wave_kernel_c2_w512_k64.md"),
-    ("c2_w1024", 128, "f32", "pairs"): (5368919011, "profiles/rtopk_wave_kernel_c2_w1024_k128.md"),
-    ("c3_ties", 32, "f32", "pairs"): (2841777274, "profiles/rtopk_wave_kernel_c3_ties_k32.md"),
-    ("c4_wide", 64, "f32", "pairs"): (1107429349, "profiles/rtopk_wave_kernel_c4_wide_k64.md"),
-    ("x_wide32k", 256, "f32", "pairs"): (1090836193, "profiles/rtopk_block_kernel_x_wide32k_k256.md"),
+    ("c1_maxk", 32, "f32", "pairs"): (1342397495, "profiles/rtopk_wave_kernel_c1_maxk_k32.md"),
+    ("c1_maxk", 32, "bf16", "pairs"): (738399789, "profiles/rtopk_wave_kernel_c1_maxk_k32dtypebf16.md"),
+    ("c1_maxk", 32, "f32", "dense"): (2147639472, "profiles/rtopk_dense_kernel_c1_maxk_k32opdense.md"),
+    ("c2_w128", 16, "f32", "pairs"): (671333304, "profiles/rtopk_wave_kernel_c2_w128_k16.md"),
+    ("c2_w512", 64, "f32", "pairs"): (2684437542, "profiles/rtopk_wave_kernel_c2_w512_k64.md"),
+    ("c2_w1024", 128, "f32", "pairs"): (5368919951, "profiles/rtopk_wave_kernel_c2_w1024_k128.md"),
+    ("c3_ties", 32, "f32", "pairs"): (2841775990, "profiles/rtopk_wave_kernel_c3_ties_k32.md"),
+    ("c4_wide", 64, "f32", "pairs"): (1107526387, "profiles/rtopk_wave_kernel_c4_wide_k64.md"),
+    ("x_wide32k", 256, "f32", "pairs"): (1090981092, "profiles/rtopk_block_kernel_x_wide32k_k256.md"),
 }
 
 
