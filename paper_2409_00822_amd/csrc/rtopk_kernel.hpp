@@ -458,7 +458,10 @@ __device__ __forceinline__ void lds_store_masked(uint64_t mask, uint32_t addr, f
 // kBandRegs registers per lane and the remaining steps compare those instead of the whole row:
 //   #{key >= t} = #{key >= hi} + #{band members with key >= t}    for every lo <= t < hi.
 // Thresholds, counts and therefore the result are exactly those of the full-width search.
-constexpr int kBandRegs = 4;
+#ifndef RTOPK_BAND_REGS
+#define RTOPK_BAND_REGS 4
+#endif
+constexpr int kBandRegs = RTOPK_BAND_REGS;
 // Which kernels narrow: those for rows of 24 or more values per lane, which are the widths that go one
 // row to a wavefront, so that the row's staging area is still unused while it is searched.
 constexpr bool narrows(int E, int /*mode*/) { return E >= 24; }
@@ -468,22 +471,31 @@ constexpr bool narrows(int E, int /*mode*/) { return E >= 24; }
 // wait is written out because the compiler does not track LDS operations inside asm blocks.
 template <bool NEG>
 __device__ __forceinline__ void load_band(uint32_t scratch, int lane, uint32_t nb, float (&y)[kBandRegs]) {
-  static_assert(kBandRegs == 4, "four values per lane");
-  float v0, v1, v2, v3;
+  static_assert(kBandRegs == 4 || kBandRegs == 8, "four or eight values per lane");
+  const float none = NEG ? __builtin_inff() : -__builtin_inff();
+  float v[8];
   asm volatile(
       "ds_read_b32 %0, %4\n\t"
       "ds_read_b32 %1, %4 offset:256\n\t"
       "ds_read_b32 %2, %4 offset:512\n\t"
       "ds_read_b32 %3, %4 offset:768\n\t"
       "s_waitcnt lgkmcnt(0)"
-      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
       : "v"(scratch + (uint32_t)lane * 4u)
       : "memory");
-  const float none = NEG ? __builtin_inff() : -__builtin_inff();
-  y[0] = (uint32_t)lane < nb ? v0 : none;
-  y[1] = (uint32_t)lane + 64u < nb ? v1 : none;
-  y[2] = (uint32_t)lane + 128u < nb ? v2 : none;
-  y[3] = (uint32_t)lane + 192u < nb ? v3 : none;
+  if constexpr (kBandRegs == 8) {
+    asm volatile(
+        "ds_read_b32 %0, %4 offset:1024\n\t"
+        "ds_read_b32 %1, %4 offset:1280\n\t"
+        "ds_read_b32 %2, %4 offset:1536\n\t"
+        "ds_read_b32 %3, %4 offset:1792\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(scratch + (uint32_t)lane * 4u)
+        : "memory");
+  }
+#pragma unroll
+  for (int j = 0; j < kBandRegs; ++j) y[j] = (uint32_t)lane + 64u * j < nb ? v[j] : none;
 }
 
 // Gathers the row's band members through `scratch` (kBandRegs*64 floats of LDS) into y[]; lanes beyond
