@@ -124,3 +124,33 @@ def test_generated_search_loops_are_current():
     committed = open(os.path.join(csrc, "rtopk_search_loops.inc")).read()
     gen.main()  # rewrites the file only if it differs
     assert open(os.path.join(csrc, "rtopk_search_loops.inc")).read() == committed
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path, lib):
+    # the boundary is a C ABI: the header must compile as C99, and a C program must link against the
+    # library and reach the host-only entry points
+    import shutil
+    import subprocess
+
+    import paper_2409_00822_amd as R
+
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_rtopk.c"
+    src.write_text(
+        '#include "rtopk.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "  if (rtopk_max_m() != 65536 || rtopk_version() < 100) return 1;\n"
+        "  /* argument errors are reported on the host, before any launch */\n"
+        "  if (rtopk_rowwise(0, 4, 256, 32, 8, 0, 0, 0) != RTOPK_ERR_NULL_POINTER) return 2;\n"
+        "  if (rtopk_rowwise_exact((const float*)64, 4, 256, 300, (float*)64, (int32_t*)64, 0) != RTOPK_ERR_BAD_SHAPE) return 3;\n"
+        "  if (rtopk_maxk_dense(0, 0, 256, 32, -1, 0, 0) != RTOPK_OK) return 4;\n"
+        '  printf("%s\\n", rtopk_status_string(RTOPK_ERR_M_TOO_LARGE));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "use_rtopk"
+    libdir = os.path.dirname(R.lib_path())
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                           "-o", str(exe), "-L", libdir, "-l:librtopk.so", "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, (out.returncode, out.stderr)
+    assert "row width" in out.stdout
