@@ -254,6 +254,21 @@ def main():
                "sample": f"all {N} rows of the same input, exact mode (nth_element per row, OpenMP over rows), "
                          f"median of {n_pass} passes after 1 warm-up ({sum(reps):.1f} s of CPU work)"}
         log(f"  oracle: {t_cpu:.3f} s per pass on {cpu['cores']} threads")
+        # the same on one thread, on the first 65536 rows
+        if not half and N >= 65536:
+            threads = oracle.num_threads()
+            oracle.set_num_threads(1)
+            try:
+                sl = x_host[:65536]
+                oracle.topk_exact(sl, k)
+                t1 = []
+                for _ in range(5):
+                    t0 = time.perf_counter()
+                    oracle.topk_exact(sl, k)
+                    t1.append(time.perf_counter() - t0)
+                cpu["one_thread_rows_per_s"] = 65536 / statistics.median(t1)
+            finally:
+                oracle.set_num_threads(threads)
 
     traffic = MEASURED_TRAFFIC.get((args.workload, k, args.dtype, args.op), (None, None)) if N == cfg["N"] else (None, None)
     rows_per_s = N * args.steps / wall_e
