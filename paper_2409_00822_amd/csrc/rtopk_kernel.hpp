@@ -214,6 +214,9 @@ __device__ __forceinline__ void compact_masks(const float (&x)[G * NG], const ui
     // every call site, are computed up front and stay live through the whole search.
     int ln = lane;
     if constexpr (NG > 4) asm volatile("" : "+v"(ln));
+    if constexpr (CUT && NG > 1) {
+      if (base >= (uint32_t)limit) break;  // the first `limit` candidates are all in earlier groups
+    }
     uint64_t m[G];
 #pragma unroll
     for (int c = 0; c < G; ++c) {
