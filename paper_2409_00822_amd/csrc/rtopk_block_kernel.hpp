@@ -247,8 +247,8 @@ __global__ void __launch_bounds__(W * kWave)
       __syncthreads();
       if (wave == 0) {
         float all[kBandRegs];
-        load_band<NEG>(dst, lane, total, all);
-        search_band<MODE, NEG, DT>(all, above_all, k, eps, lo, hi, thres, hit, steps);
+        load_band<NEG, kBandRegs>(dst, lane, total, all);
+        search_band<MODE, NEG, DT, kBandRegs>(all, above_all, k, eps, lo, hi, thres, hit, steps);
         if (lane == 0) {
           s_res[0] = lo;
           s_res[1] = hi;

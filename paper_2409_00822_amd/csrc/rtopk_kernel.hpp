@@ -457,14 +457,15 @@ __device__ __forceinline__ void lds_store_masked(uint64_t mask, uint32_t addr, f
 // below lo by none.  On the rows this method is meant for that band empties fast -- the bisection is
 // over the value range, and after three to five steps it holds a few hundred of thousands of elements
 // (median 161 of 4096 after three steps and 68 after four on Laplace rows, 277 of 8192 after four on
-// normal ones) -- so once at most kBandRegs*64 elements are left they are gathered, in any order, into
-// kBandRegs registers per lane and the remaining steps compare those instead of the whole row:
+// normal ones) -- so once at most 256 (or 512) elements are left they are gathered, in any order, into
+// four (or eight) registers per lane and the remaining steps compare those instead of the whole row:
 //   #{key >= t} = #{key >= hi} + #{band members with key >= t}    for every lo <= t < hi.
 // Thresholds, counts and therefore the result are exactly those of the full-width search.
-#ifndef RTOPK_BAND_REGS
-#define RTOPK_BAND_REGS 4
-#endif
-constexpr int kBandRegs = RTOPK_BAND_REGS;
+constexpr int kBandRegs = 4;
+// Registers per lane the band is gathered into, by row width: eight for rows of 128 values per lane
+// (M = 8192: 4 % faster than four, one full-width step fewer), four otherwise (M = 4096: 4 % faster
+// than eight; the workgroup-per-row kernel likewise).
+constexpr int band_regs(int E) { return E >= 128 ? 8 : kBandRegs; }
 // Which kernels narrow: those for rows of 24 or more values per lane, which are the widths that go one
 // row to a wavefront, so that the row's staging area is still unused while it is searched.
 constexpr bool narrows(int E, int /*mode*/) { return E >= 24; }
@@ -472,9 +473,9 @@ constexpr bool narrows(int E, int /*mode*/) { return E >= 24; }
 // y[j] = the (lane + 64 j)-th of the nb floats at LDS address `scratch`, or a key of -inf beyond them.
 // The LDS queue of a wavefront is served in order, so the reads see the wavefront's earlier writes; the
 // wait is written out because the compiler does not track LDS operations inside asm blocks.
-template <bool NEG>
-__device__ __forceinline__ void load_band(uint32_t scratch, int lane, uint32_t nb, float (&y)[kBandRegs]) {
-  static_assert(kBandRegs == 4 || kBandRegs == 8, "four or eight values per lane");
+template <bool NEG, int BR>
+__device__ __forceinline__ void load_band(uint32_t scratch, int lane, uint32_t nb, float (&y)[BR]) {
+  static_assert(BR == 4 || BR == 8, "four or eight values per lane");
   const float none = NEG ? __builtin_inff() : -__builtin_inff();
   float v[8];
   asm volatile(
@@ -486,7 +487,7 @@ __device__ __forceinline__ void load_band(uint32_t scratch, int lane, uint32_t n
       : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
       : "v"(scratch + (uint32_t)lane * 4u)
       : "memory");
-  if constexpr (kBandRegs == 8) {
+  if constexpr (BR == 8) {
     asm volatile(
         "ds_read_b32 %0, %4 offset:1024\n\t"
         "ds_read_b32 %1, %4 offset:1280\n\t"
@@ -498,16 +499,16 @@ __device__ __forceinline__ void load_band(uint32_t scratch, int lane, uint32_t n
         : "memory");
   }
 #pragma unroll
-  for (int j = 0; j < kBandRegs; ++j) y[j] = (uint32_t)lane + 64u * j < nb ? v[j] : none;
+  for (int j = 0; j < BR; ++j) y[j] = (uint32_t)lane + 64u * j < nb ? v[j] : none;
 }
 
-// Gathers the row's band members through `scratch` (kBandRegs*64 floats of LDS) into y[]; lanes beyond
+// Gathers the row's band members through `scratch` (BR*64 floats of LDS) into y[]; lanes beyond
 // the band hold a key of -inf.  Returns #{key >= hi}.  The caller guarantees the band fits.
 // SPARSE: most of the lane masks are expected to be empty (a workgroup's band is spread over all its
 // wavefronts), so each is tested before it is ranked and stored.
-template <int E, bool NEG, bool SPARSE = false>
+template <int E, bool NEG, bool SPARSE = false, int BR = kBandRegs>
 __device__ __forceinline__ int gather_band(const float (&x)[E], float lo, float hi, int lane, uint32_t scratch,
-                                           float (&y)[kBandRegs], uint32_t& nb) {
+                                           float (&y)[BR], uint32_t& nb) {
   int above = 0;
   nb = 0;  // wave-uniform: band members found so far
 #pragma unroll
@@ -522,16 +523,16 @@ __device__ __forceinline__ int gather_band(const float (&x)[E], float lo, float 
     }
     if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // keep the masks of later elements from piling up
   }
-  load_band<NEG>(scratch, lane, nb, y);
+  load_band<NEG, BR>(scratch, lane, nb, y);
   return above;
 }
 
 // #{band members with key >= t}
-template <bool NEG>
-__device__ __forceinline__ int count_band(const float (&band)[kBandRegs], float t) {
+template <bool NEG, int BR>
+__device__ __forceinline__ int count_band(const float (&band)[BR], float t) {
   int cnt = 0;
 #pragma unroll
-  for (int j = 0; j < kBandRegs; ++j) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keyof<NEG>(band[j]) >= t));
+  for (int j = 0; j < BR; ++j) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keyof<NEG>(band[j]) >= t));
   return cnt;
 }
 
@@ -539,8 +540,8 @@ __device__ __forceinline__ int count_band(const float (&band)[kBandRegs], float 
 // exact mode until a step counts k or the midpoint is no longer strictly inside (lo, hi) -- the state
 // the full-width loop detects, one or two steps later, by its midpoint repeating -- and the
 // precision-bounded mode with its own guard and step count.
-template <int MODE, bool NEG, int DT>
-__device__ __forceinline__ void search_band(const float (&band)[kBandRegs], int above, int k, float eps, float& lo,
+template <int MODE, bool NEG, int DT, int BR>
+__device__ __forceinline__ void search_band(const float (&band)[BR], int above, int k, float eps, float& lo,
                                             float& hi, float& thres, bool& hit, int& steps) {
   for (;;) {
     if constexpr (MODE == kEps) {
@@ -550,7 +551,7 @@ __device__ __forceinline__ void search_band(const float (&band)[kBandRegs], int 
     if (!(mid > lo && mid < hi)) break;
     thres = mid;
     ++steps;
-    const int cnt = above + count_band<NEG>(band, thres);
+    const int cnt = above + count_band<NEG, BR>(band, thres);
     if (cnt == k) {
       hit = true;
       break;
@@ -600,6 +601,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
   constexpr bool KEEP = E <= 8;                       // masks of the last step stay in scalar registers
   // wider rows: ACC of the E elements are counted per lane, the rest by mask popcount
   constexpr int ACC = KEEP ? 0 : RTOPK_ACC_OF(E);
+  constexpr int BR = band_regs(E);  // registers per lane of a gathered band (see gather_band)
   uint64_t m[KEEP ? E : 1];
   auto count = [&](float t) -> int {
     if constexpr (KEEP) {
@@ -619,7 +621,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       hit = search_exact_asm(x, lo, hi, k, m, std::integral_constant<bool, NEG>(), std::integral_constant<int, DT>());
     } else {
       // cnt_lo = #{key >= lo} and a lower bound cnt_hi of #{key >= hi} bound the band [lo, hi) from
-      // above; once it fits kBandRegs registers per lane the search narrows to it (see gather_band).
+      // above; once it fits BR registers per lane the search narrows to it (see gather_band).
       constexpr bool NARROW = narrows(E, MODE);
       int cnt_lo = M, cnt_hi = 0;
       bool narrow = false;
@@ -637,7 +639,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
         if constexpr (NARROW) {
           cnt_lo = cnt < k ? cnt_lo : cnt;
           cnt_hi = cnt < k ? cnt : cnt_hi;
-          if (cnt_lo - cnt_hi <= kBandRegs * kWave) {
+          if (cnt_lo - cnt_hi <= BR * kWave) {
             narrow = true;
             break;
           }
@@ -652,7 +654,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
         if constexpr (NARROW) {
           cnt_lo = cnt < k ? cnt_lo : cnt;
           cnt_hi = cnt < k ? cnt : cnt_hi;
-          if (cnt_lo - cnt_hi <= kBandRegs * kWave) {
+          if (cnt_lo - cnt_hi <= BR * kWave) {
             narrow = true;
             break;
           }
@@ -660,11 +662,11 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       }
       if constexpr (NARROW) {
         if (narrow) {
-          float band[kBandRegs];
+          float band[BR];
           uint32_t nb;
-          const int above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band, nb);
+          const int above = gather_band<E, NEG, false, BR>(x, lo, hi, lane, stage_addr, band, nb);
           int unused_steps = 0;
-          search_band<kExact, NEG, DT>(band, above, k, 0.0f, lo, hi, thres, hit, unused_steps);
+          search_band<kExact, NEG, DT, BR>(band, above, k, 0.0f, lo, hi, thres, hit, unused_steps);
         }
       }
     }
@@ -691,7 +693,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
     constexpr bool NARROW = narrows(E, MODE);
     int cnt_lo = M, cnt_hi = 0, above = 0;
     bool narrow = false;
-    float band[kBandRegs];
+    float band[BR];
     while (hi - lo > eps) {
       const float mid = (lo + hi) * 0.5f;
       if (!(mid > lo && mid < hi)) break;
@@ -699,7 +701,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       ++steps;
       int cnt;
       if (NARROW && narrow) {
-        cnt = above + count_band<NEG>(band, thres);
+        cnt = above + count_band<NEG, BR>(band, thres);
       } else {
         cnt = count(thres);
       }
@@ -712,9 +714,9 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
         if (!narrow) {
           cnt_lo = cnt < k ? cnt_lo : cnt;
           cnt_hi = cnt < k ? cnt : cnt_hi;
-          if (cnt_lo - cnt_hi <= kBandRegs * kWave) {
+          if (cnt_lo - cnt_hi <= BR * kWave) {
             uint32_t nb;
-            above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band, nb);
+            above = gather_band<E, NEG, false, BR>(x, lo, hi, lane, stage_addr, band, nb);
             narrow = true;
           }
         }
@@ -737,11 +739,11 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       constexpr bool NARROW = narrows(E, MODE);
       int cnt_lo = M, cnt_hi = 0, above = 0;
       bool narrow = false;
-      float band[kBandRegs];
+      float band[BR];
       for (int it = 0; it < max_iter; ++it) {
         const float thres = (lo + hi) * 0.5f;
         if (NARROW && narrow) {
-          cnt = above + count_band<NEG>(band, thres);
+          cnt = above + count_band<NEG, BR>(band, thres);
         } else {
           cnt = count(thres);
         }
@@ -754,9 +756,9 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
             cnt_lo = cnt < k ? cnt_lo : cnt;
             cnt_hi = cnt < k ? cnt : cnt_hi;
             // the gather costs about as much as three full-width steps: only when more remain
-            if (cnt_lo - cnt_hi <= kBandRegs * kWave && it + 6 < max_iter) {
+            if (cnt_lo - cnt_hi <= BR * kWave && it + 6 < max_iter) {
               uint32_t nb;
-              above = gather_band<E, NEG>(x, lo, hi, lane, stage_addr, band, nb);
+              above = gather_band<E, NEG, false, BR>(x, lo, hi, lane, stage_addr, band, nb);
               narrow = true;
             }
           }
@@ -893,7 +895,7 @@ __global__ void __launch_bounds__(256)
   const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
   // per wavefront: R*k pairs, and at least the band scratch where the exact search of a wide row uses it
   static_assert(!narrows(E, MODE) || R == 1, "the band scratch reuses the staging area of the wavefront's only row");
-  constexpr int kMinPairs = narrows(E, MODE) ? kBandRegs * kWave / 2 : 0;
+  constexpr int kMinPairs = narrows(E, MODE) ? band_regs(E) * kWave / 2 : 0;
   const int pairs_per_wave = R * k > kMinPairs ? R * k : kMinPairs;
   uint2* stage = stage_all + (size_t)wave * pairs_per_wave;
 
@@ -994,14 +996,14 @@ template <int G, int NG, int R, bool FULL, int MODE>
 __global__ void __launch_bounds__(256)
     rtopk_dense_kernel(const float* __restrict__ in, int64_t N, int M, int k, int max_iter, float* __restrict__ out) {
   constexpr int E = G * NG;
-  extern __shared__ uint2 band_scratch[];  // [waves per block][kBandRegs * 64 floats], wide rows in exact mode only
+  extern __shared__ uint2 band_scratch[];  // [waves per block][band_regs(E) * 64 floats], wide rows only
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int waves_per_block = (int)(blockDim.x >> 6);
   const int64_t r0 = ((int64_t)blockIdx.x * waves_per_block + wave) * R;
   if (r0 >= N) return;
   const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
-  uint2* scratch = band_scratch + (size_t)wave * (kBandRegs * kWave / 2);
+  uint2* scratch = band_scratch + (size_t)wave * (band_regs(E) * kWave / 2);
 
   float x[R][E];
 #pragma unroll
@@ -1041,7 +1043,7 @@ hipError_t launch_dense(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  const size_t lds = narrows(G * NG, MODE) ? (size_t)waves * kBandRegs * kWave * sizeof(float) : 0;
+  const size_t lds = narrows(G * NG, MODE) ? (size_t)waves * band_regs(G * NG) * kWave * sizeof(float) : 0;
   hipLaunchKernelGGL((rtopk_dense_kernel<G, NG, R, FULL, MODE>), dim3((unsigned)blocks), dim3(waves * kWave), lds,
                      a.stream, static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter,
                      static_cast<float*>(a.out_vals));
@@ -1055,7 +1057,7 @@ hipError_t launch(const LaunchArgs& a) {
   // LDS per wavefront: R*k staged pairs of 8 bytes; at most 64 KiB per block.
   size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
   // the exact search of wide rows gathers its band through the (not yet used) staging area
-  if (narrows(G * NG, MODE) && per_wave < kBandRegs * kWave * sizeof(float)) per_wave = kBandRegs * kWave * sizeof(float);
+  if (narrows(G * NG, MODE) && per_wave < band_regs(G * NG) * kWave * sizeof(float)) per_wave = band_regs(G * NG) * kWave * sizeof(float);
   // one wavefront per workgroup, except where a wavefront stages 8 KiB or more of pairs: there four
   // per workgroup measured 7 % faster (2^20 x 256, k = 128: 387 -> 360 us), while at 4 KiB and below
   // one per workgroup is the faster by 3-11 %
