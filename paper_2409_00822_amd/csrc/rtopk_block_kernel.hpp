@@ -82,10 +82,10 @@ __global__ void __launch_bounds__(W * kWave)
   __shared__ int s_cnt[2][W];          // per-wavefront counts of a search step, double buffered
   __shared__ int s_tab[2][T];          // candidates per cell of class A / class B, then their exclusive prefixes
   // narrowing of Algorithm 1's search (see gather_band): per-wavefront gather areas, the whole row's
-  // band, its per-wavefront sizes, and what wavefront 0 hands back after finishing the search alone
+  // band, its size, and what wavefront 0 hands back after finishing the search alone
   __shared__ float s_gather[W][kBandRegs * kWave];
   __shared__ float s_band[kBandRegs * kWave];
-  __shared__ int s_nb[W], s_above[W];
+  __shared__ int s_tot[2];  // band members / elements at or above hi, summed over the wavefronts
   __shared__ float s_res[3];
   __shared__ int s_resi[2];
 
@@ -115,6 +115,10 @@ __global__ void __launch_bounds__(W * kWave)
     if (lane == 0) {
       s_hi[wave] = wmax;
       s_nlo[wave] = -wmin;
+    }
+    if (threadIdx.x == 0) {
+      s_tot[0] = 0;
+      s_tot[1] = 0;
     }
     __syncthreads();
     float a = s_hi[0], b = s_nlo[0];
@@ -224,20 +228,13 @@ __global__ void __launch_bounds__(W * kWave)
       float band[kBandRegs];
       uint32_t nb;
       const int above = gather_band<E, NEG, true>(x, lo, hi, lane, (uint32_t)(uintptr_t)s_gather[wave], band, nb);
+      // a place in the row's band for this wavefront's members (any order will do)
+      uint32_t off = 0;
       if (lane == 0) {
-        s_nb[wave] = (int)nb;
-        s_above[wave] = above;
+        off = (uint32_t)atomicAdd(&s_tot[0], (int)nb);
+        atomicAdd(&s_tot[1], above);
       }
-      __syncthreads();
-      uint32_t off = 0, total = 0;
-      int above_all = 0;
-#pragma unroll
-      for (int w = 0; w < W; ++w) {
-        const uint32_t n = (uint32_t)s_nb[w];
-        off += w < wave ? n : 0u;
-        total += n;
-        above_all += s_above[w];
-      }
+      off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
       const uint32_t dst = (uint32_t)(uintptr_t)s_band;
 #pragma unroll
       for (int j = 0; j < kBandRegs; ++j) {
@@ -247,6 +244,8 @@ __global__ void __launch_bounds__(W * kWave)
       __syncthreads();
       if (wave == 0) {
         float all[kBandRegs];
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readfirstlane(s_tot[0]);
+        const int above_all = __builtin_amdgcn_readfirstlane(s_tot[1]);
         load_band<NEG, kBandRegs>(dst, lane, total, all);
         search_band<MODE, NEG, DT, kBandRegs>(all, above_all, k, eps, lo, hi, thres, hit, steps);
         if (lane == 0) {
