@@ -47,6 +47,10 @@ def _load():
         lib.oracle_alg1.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                     ctypes.c_int32, f32p, i32p, i32p]
         lib.oracle_alg1.restype = ctypes.c_int
+        lib.oracle_maxk_backward.argtypes = [f32p, i32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, f32p]
+        lib.oracle_maxk_backward.restype = ctypes.c_int
+        lib.oracle_maxk_backward_gather.argtypes = [f32p, i32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, f32p]
+        lib.oracle_maxk_backward_gather.restype = ctypes.c_int
         lib.oracle_mean_overlap.argtypes = [i32p, i32p, ctypes.c_int64, ctypes.c_int32]
         lib.oracle_mean_overlap.restype = ctypes.c_double
         lib.oracle_num_threads.restype = ctypes.c_int
@@ -193,4 +197,34 @@ def maxk_dense(x: np.ndarray, k: int, max_iter: int = -1) -> np.ndarray:
     out = np.zeros_like(x)
     rows = np.arange(x.shape[0])[:, None]
     out[rows, idx] = x[rows, idx]
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Backward edge of the MaxK non-linearity (Section 1 / Fig. 1, Section 4.3): the derivative of "keep
+# the k selected columns, zero the rest" with respect to the row is the 0/1 selection mask.
+# ---------------------------------------------------------------------------------------------
+def maxk_backward(grad_vals: np.ndarray, idx: np.ndarray, M: int) -> np.ndarray:
+    """Scatter form: gradients of the k kept values [N, k] -> gradient of the dense row [N, M]
+    (zero except at the saved columns idx [N, k])."""
+    g = np.ascontiguousarray(grad_vals, dtype=np.float32)
+    i = np.ascontiguousarray(idx, dtype=np.int32)
+    assert g.ndim == 2 and g.shape == i.shape
+    N, k = g.shape
+    out = np.empty((N, M), dtype=np.float32)
+    if _load().oracle_maxk_backward(_f32(g), _i32(i), N, M, k, _f32(out)) != 0:
+        raise ValueError("oracle_maxk_backward: bad arguments")
+    return out
+
+
+def maxk_backward_gather(grad_out: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """Gather form: dense gradient rows [N, M] -> their entries at the saved columns idx [N, k]."""
+    g = _check_in(grad_out)
+    i = np.ascontiguousarray(idx, dtype=np.int32)
+    N, M = g.shape
+    assert i.ndim == 2 and i.shape[0] == N
+    k = i.shape[1]
+    out = np.empty((N, k), dtype=np.float32)
+    if _load().oracle_maxk_backward_gather(_f32(g), _i32(i), N, M, k, _f32(out)) != 0:
+        raise ValueError("oracle_maxk_backward_gather: bad arguments")
     return out

@@ -22,6 +22,14 @@
 //                          Pinned by two independent decoders for the widening, brute force and a
 //                          library top-k for the exact mode, hand traces and the grid
 //                          characterisation for Algorithm 2 (tests/test_oracle_pins_16bit.py).
+//   oracle_maxk_backward,  the backward edge of the MaxK non-linearity (Section 1 / Fig. 1; Section 4.3 puts
+//   oracle_maxk_backward_gather
+//                          the selection inside MaxK-GNN training): the derivative of "keep the k selected
+//                          columns, zero the rest" is the same mask, so gradients at the k saved columns
+//                          are scattered into a zero row, or gathered out of a dense gradient row.
+//                          Pinned by automatic differentiation through a library gather (scatter form),
+//                          by the library gather itself, and by plain loops under ties
+//                          (tests/test_oracle_pins.py).
 //   oracle_alg1            Algorithm 1, step by step, fp32, with the readings
 //                          listed below.  Pinned by Tables 1 and 5 (exit
 //                          iterations), by Eq. 4, and by equality with the
@@ -261,7 +269,7 @@ int oracle_alg1(const float* in, int64_t N, int32_t M, int32_t k, float eps_rel,
   return 0;
 }
 
-// The k SMALLEST values per row (Section 3: "largest (or smallest)").  Exact: the plain definition,
+// The k SMALLEST values per row (Section 3 poses the problem for either end of the order).  Exact: the plain definition,
 // pairs ordered by value ascending, then column ascending.
 int oracle_topk_exact_smallest(const float* in, int64_t N, int32_t M, int32_t k, float* out_vals, int32_t* out_idx) {
   if (N < 0 || M < 1 || k < 1 || k > M) return -1;
@@ -285,8 +293,8 @@ int oracle_topk_exact_smallest(const float* in, int64_t N, int32_t M, int32_t k,
   return 0;
 }
 
-// Early stopping for the k smallest: Algorithm 2 applied to the negated row ("without loss of
-// generality"), with the original values written out.
+// Early stopping for the k smallest: Algorithm 2 applied to the negated row (the paper develops the
+// largest case only and notes that nothing is lost by that), with the original values written out.
 int oracle_topk_earlystop_smallest(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter,
                                    float* out_vals, int32_t* out_idx) {
   if (N < 0 || M < 1 || k < 1 || k > M || max_iter < 0) return -1;
@@ -297,6 +305,45 @@ int oracle_topk_earlystop_smallest(const float* in, int64_t N, int32_t M, int32_
   if (rc != 0) return rc;
   for (int64_t r = 0; r < N; ++r)
     for (int32_t j = 0; j < k; ++j) out_vals[r * (int64_t)k + j] = in[r * (int64_t)M + out_idx[r * (int64_t)k + j]];
+  return 0;
+}
+
+// Backward edge of the MaxK non-linearity (Section 1 / Fig. 1: the row-wise top-k acts as the
+// non-linearity of a MaxK-GNN layer; Section 4.3 measures it inside training).  Forward, in dense form:
+// y[r][c] = x[r][c] for the k selected columns of row r and 0 elsewhere, so dy/dx is that same 0/1 mask.
+//
+// Scatter form: the gradient arrives for the k kept values only (grad_vals[N][k], in the order of
+// idx[N][k]); the gradient with respect to the dense input row is zero except at the saved columns.
+// Columns outside [0, M) are ignored.  Columns are expected to be distinct within a row (the forward
+// pass writes them strictly ascending).
+int oracle_maxk_backward(const float* grad_vals, const int32_t* idx, int64_t N, int32_t M, int32_t k, float* grad_in) {
+  if (N < 0 || M < 1 || k < 1 || k > M) return -1;
+  if (N > 0 && (!grad_vals || !idx || !grad_in)) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < N; ++r) {
+    float* row = grad_in + r * (int64_t)M;
+    for (int32_t c = 0; c < M; ++c) row[c] = 0.0f;
+    for (int32_t j = 0; j < k; ++j) {
+      const int32_t c = idx[r * (int64_t)k + j];
+      if (c >= 0 && c < M) row[c] = grad_vals[r * (int64_t)k + j];
+    }
+  }
+  return 0;
+}
+
+// Gather form: the gradient arrives as a dense row (grad_out[N][M]); what flows back through the k
+// kept values is its entries at the saved columns.  A column outside [0, M) yields 0.
+int oracle_maxk_backward_gather(const float* grad_out, const int32_t* idx, int64_t N, int32_t M, int32_t k,
+                                float* grad_vals) {
+  if (N < 0 || M < 1 || k < 1 || k > M) return -1;
+  if (N > 0 && (!grad_out || !idx || !grad_vals)) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < N; ++r) {
+    for (int32_t j = 0; j < k; ++j) {
+      const int32_t c = idx[r * (int64_t)k + j];
+      grad_vals[r * (int64_t)k + j] = (c >= 0 && c < M) ? grad_out[r * (int64_t)M + c] : 0.0f;
+    }
+  }
   return 0;
 }
 
