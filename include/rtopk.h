@@ -18,14 +18,15 @@
  *                 (int32_t, or uint8_t in the *_u8 variants, which require M <= 256: this is the
  *                 compressed row -- k values plus k byte-wide columns -- that MaxK-GNN's sparse
  *                 aggregation consumes, Section 1 / Fig. 1).
- *  - Input and output buffers must not overlap.
+ *  - Input and output buffers must not overlap (checked on the host: RTOPK_ERR_OVERLAP).
  *  - Ties are broken towards the lower column index.
  *  - Preconditions that are NOT checked: every input is finite and |v| < FLT_MAX / 2 (so that
  *    min + max cannot overflow).  With NaN or infinities the selection is unspecified, but the call
  *    still terminates and writes only inside the output buffers.
  *  - Return value: RTOPK_OK (0) when the work was enqueued (or N == 0: nothing to do), otherwise a
  *    negative RTOPK_ERR_* code; every argument check happens on the host before any launch, and on
- *    error nothing was enqueued.  Faults of the asynchronous work surface at the caller's next
+ *    error nothing was enqueued.  A pending error of the caller's own earlier HIP calls is neither
+ *    reported nor cleared.  Faults of the asynchronous work surface at the caller's next
  *    synchronisation, as with any HIP launch.
  *  - Limits: 1 <= k <= M <= rtopk_max_m() = 65536 (256 in the *_u8 variants); 0 <= N; N * M and N * k
  *    must fit in int64_t.  Rows wider than 8192 columns are handled by one workgroup per row, and
@@ -48,7 +49,8 @@ enum {
   RTOPK_ERR_M_TOO_LARGE = -4,   /* M > rtopk_max_m(), or M > 256 in a *_u8 variant */
   RTOPK_ERR_MISALIGNED = -5,    /* a pointer is not aligned to its element size */
   RTOPK_ERR_LAUNCH = -6,        /* the HIP runtime refused the launch */
-  RTOPK_ERR_BAD_EPSILON = -7    /* eps_rel is negative or NaN */
+  RTOPK_ERR_BAD_EPSILON = -7,   /* eps_rel is negative or NaN */
+  RTOPK_ERR_OVERLAP = -8        /* the input shares bytes with an output, or two outputs with each other */
 };
 
 /*
@@ -56,13 +58,15 @@ enum {
  *   lo = min(row), hi = max(row); repeat max_iter times: thres = (lo + hi) * 0.5f in fp32,
  *   cnt = #{v >= thres}, cnt < k ? hi = thres : lo = thres; emit the first k columns with v >= lo.
  * max_iter == 0 is legal and returns the first k columns.  The result is bit-identical to a scalar
- * fp32 evaluation of those steps.
+ * fp32 evaluation of those steps.  Each step halves hi - lo, so after at most ~300 steps on finite fp32
+ * input the rounded midpoint equals lo or hi and further steps change nothing: a max_iter above 512 is
+ * run as 512, with bit-identical output (a caller may pass INT32_MAX for "no early stop").
  */
 int rtopk_rowwise(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out_vals,
                   int32_t* out_idx, void* stream);
 
 /*
- * Exact selection: Algorithm 1 with epsilon = 0 (Section 3.1: "becomes an exact top-k selection").
+ * Exact selection: Algorithm 1 with epsilon = 0, which Section 3.1 identifies with exact top-k.
  * The search runs until an iteration counts exactly k elements, or until no fp32 value lies strictly
  * between lo and hi; then everything >= hi is taken and the lowest columns of [lo, hi) fill up to k.
  * The result equals the plain definition of top-k with the lower column winning ties.
@@ -78,7 +82,8 @@ int rtopk_rowwise_exact_u8(const float* in, int64_t N, int32_t M, int32_t k, flo
 
 /*
  * Precision-bounded selection: Algorithm 1 with epsilon = eps_rel * |max(row)| (Section 3.1: epsilon
- * bounds the width of the "borderline" and with it the number of steps; Appendix B, Fig. 7 sweeps it).
+ * bounds how wide the band of undecided elements around the k-th value may stay, and with it the
+ * number of steps; Appendix B, Fig. 7 sweeps it).
  * The search ends when a step counts exactly k, when hi - lo <= epsilon, or when no fp32 value lies
  * strictly between lo and hi.  Everything >= hi is then taken, and the lowest columns of [lo, hi) fill
  * up to k, so every selected value is >= (k-th largest) - epsilon and every rejected one is
@@ -92,8 +97,8 @@ int rtopk_rowwise_eps(const float* in, int64_t N, int32_t M, int32_t k, float ep
                       int32_t* out_idx, int32_t* out_iters, void* stream);
 
 /*
- * The k SMALLEST values per row (Section 3: the row-wise operation finds "the largest (or smallest)
- * k elements"; the paper develops the largest case without loss of generality).  Defined as the two
+ * The k SMALLEST values per row (Section 3 states the row-wise problem for either end of the order and
+ * develops the largest case only).  Defined as the two
  * operations above applied to the negated row, with the original values written out: Algorithm 2's
  * thresholds are midpoints of the negated minimum and maximum, counts are of v <= -thres.  Ties go
  * to the lower column; columns ascend; int32 columns.
@@ -127,9 +132,40 @@ int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k
  * The selected columns are exactly those of rtopk_rowwise_exact (max_iter < 0) or of
  * rtopk_rowwise with that max_iter (max_iter >= 0).  `in` and `out` are [N][M] fp32, dense,
  * row-major, 4-byte aligned (fastest when both are 16-byte aligned and M is a multiple of 4), and must
- * not overlap.  One launch; the row is read once and written once, nothing else touches memory.
+ * not overlap (RTOPK_ERR_OVERLAP).  One launch; the row is read once and written once, nothing else
+ * touches memory.
  */
 int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out, void* stream);
+
+/*
+ * Backward edge of the MaxK non-linearity (Section 1 and Fig. 1: the row-wise top-k is the non-linearity
+ * of a MaxK-GNN layer; Section 4.3 measures it inside MaxK-GNN training).  Forward, a row keeps its k
+ * selected entries and every other entry becomes zero, so the derivative with respect to the row is
+ * that 0/1 mask, and with the columns the forward pass saved the backward step is data movement:
+ *
+ *   rtopk_maxk_backward        : grad_in[r][c] = grad_vals[r][j] where c == idx[r][j], 0.0f elsewhere
+ *                                (the gradient of the k kept values, scattered into the dense row);
+ *   rtopk_maxk_backward_gather : grad_vals[r][j] = grad_out[r][idx[r][j]]
+ *                                (the entries of a dense gradient row that flow back through the k kept values).
+ *
+ *   idx       : [N][k] columns as written by rtopk_rowwise* (int32_t, or uint8_t in the *_u8 variants,
+ *               which require M <= 256), read-only.  Columns of a row must be distinct (any order); a
+ *               column outside [0, M) is ignored by the scatter and yields 0.0f in the gather, so no
+ *               index value can make the kernels touch memory outside the buffers.
+ *   grad_vals : [N][k] fp32, row-major (input of the scatter, output of the gather).
+ *   grad_in / grad_out : [N][M] fp32, dense, row-major (fastest when 16-byte aligned and M % 4 == 0).
+ * All pointers are device pointers, 4-byte aligned (uint8 columns: any alignment); the dense array must
+ * not overlap the others, and the gather's output must not overlap idx (RTOPK_ERR_OVERLAP).  One
+ * launch per call; every byte of the inputs is read once and every byte of the output written once.
+ */
+int rtopk_maxk_backward(const float* grad_vals, const int32_t* idx, int64_t N, int32_t M, int32_t k, float* grad_in,
+                        void* stream);
+int rtopk_maxk_backward_u8(const float* grad_vals, const uint8_t* idx, int64_t N, int32_t M, int32_t k, float* grad_in,
+                           void* stream);
+int rtopk_maxk_backward_gather(const float* grad_out, const int32_t* idx, int64_t N, int32_t M, int32_t k,
+                               float* grad_vals, void* stream);
+int rtopk_maxk_backward_gather_u8(const float* grad_out, const uint8_t* idx, int64_t N, int32_t M, int32_t k,
+                                  float* grad_vals, void* stream);
 
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* rtopk_status_string(int status);

@@ -10,6 +10,8 @@ from .rtopk import (  # noqa: F401
     lib_path,
     load_library,
     rtopk_max_m,
+    rtopk_maxk_backward,
+    rtopk_maxk_backward_gather,
     rtopk_maxk_dense,
     rtopk_rowwise,
     rtopk_rowwise_bf16,

@@ -9,11 +9,10 @@
 
 namespace {
 
-constexpr int kMaxM = 65536;     // one workgroup per row beyond kMaxWaveM
-constexpr int kMaxWaveM = 8192;  // widest row one wavefront holds in registers
-constexpr int kVersion = 500;  // 0.5.0
+constexpr int kVersion = 600;  // 0.6.0
 
-inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline uintptr_t addr(const void* p) { return reinterpret_cast<uintptr_t>(p); }
+inline bool aligned(const void* p, uintptr_t a) { return rtopk::is_aligned(addr(p), a); }
 
 // Shared body of the selection entry points.
 //   mode: rtopk::kEarly (Algorithm 2, max_iter steps), kExact (Algorithm 1, epsilon = 0) or
@@ -26,11 +25,22 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
   if (mode == rtopk::kEarly && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
   if (mode == rtopk::kEps && !(eps_rel >= 0.0f)) return RTOPK_ERR_BAD_EPSILON;
-  if (M > kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > rtopk::kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > rtopk::kMaxWaveM && N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row: 2^31 - 1 rows
   if (N == 0) return RTOPK_OK;
   if (!in || !out_vals || !out_idx) return RTOPK_ERR_NULL_POINTER;
   if (!aligned(in, esz) || !aligned(out_vals, esz) || (!u8 && !aligned(out_idx, 4)) || !aligned(out_iters, 4))
     return RTOPK_ERR_MISALIGNED;
+  {
+    // the input must not share a byte with any output, nor the outputs with one another
+    const uint64_t n_in = (uint64_t)N * (uint64_t)M * esz, n_v = (uint64_t)N * (uint64_t)k * esz;
+    const uint64_t n_i = (uint64_t)N * (uint64_t)k * (u8 ? 1 : 4), n_t = out_iters ? (uint64_t)N * 4 : 0;
+    const uintptr_t p[4] = {addr(in), addr(out_vals), addr(out_idx), addr(out_iters)};
+    const uint64_t n[4] = {n_in, n_v, n_i, n_t};
+    for (int i = 0; i < 4; ++i)
+      for (int j = i + 1; j < 4; ++j)
+        if (rtopk::ranges_overlap(p[i], n[i], p[j], n[j])) return RTOPK_ERR_OVERLAP;
+  }
 
   // k == M: every column is selected.  Algorithm 2 with zero steps returns the first k columns,
   // which is that answer without a search that would otherwise run down to float resolution.
@@ -38,6 +48,8 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
     mode = rtopk::kEarly;
     max_iter = 0;
   }
+  // steps beyond the clamp cannot change the result (see kMaxIterClamp)
+  if (max_iter > rtopk::kMaxIterClamp) max_iter = rtopk::kMaxIterClamp;
 
   rtopk::LaunchArgs a;
   a.in = in;
@@ -53,71 +65,50 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   a.vec_store = (k % 4 == 0) && aligned(out_vals, 4 * esz) && aligned(out_idx, u8 ? 4 : 16);
   a.stream = static_cast<hipStream_t>(stream);
 
+  const bool plain = dtype == rtopk::kF32 && !smallest && mode != rtopk::kEps;
+  const rtopk::Shape sh = rtopk::classify(M, dtype, plain, addr(in));
   hipError_t err;
-  if (M > kMaxWaveM) {
-    if (N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row: the grid holds 2^31 - 1 rows
-    // a lane holds up to 64 values: 4 wavefronts up to 16384 columns, 8 up to 32768, 16 beyond
-    int g = 1, ng = 16, w = 16;
-    const bool plain = dtype == rtopk::kF32 && !smallest && mode != rtopk::kEps;
-    if (dtype == rtopk::kF32 && M % 4 == 0 && aligned(in, 16)) {
-      g = 4;
-      w = M <= 16384 ? 4 : (M <= 32768 ? 8 : 16);
-      ng = (plain && M <= 64 * w * 4 * 12) ? 12 : 16;
-    } else if (dtype != rtopk::kF32 && M % 8 == 0 && aligned(in, 16)) {
-      g = 8;
-      w = M <= 16384 ? 4 : (M <= 32768 ? 8 : 16);
-      ng = 8;
-    } else {
-      while (1024 * ng < M) ng <<= 1;
-    }
-    err = dtype != rtopk::kF32 ? rtopk::launch_block_h16(dtype, g, ng, w, mode, a)
-          : plain              ? rtopk::launch_block_plain(g, ng, w, mode, a)
-                               : rtopk::launch_block_variant(g, ng, w, mode, smallest, a);
-  } else if (dtype != rtopk::kF32) {
-    // 16-bit rows: the widest load whose 64 lanes the row still fills, else the scalar-load fallback
-    int g = 1, ng = 1;
-    bool full = false;
-    if (M > 256 && M % 8 == 0 && aligned(in, 16)) {
-      static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16};
-      g = 8;
-      ng = 16;
-      for (int cand : kNg) {
-        if (M <= 512 * cand) {
-          ng = cand;
-          break;
-        }
-      }
-    } else if (M > 128 && M <= 256 && M % 4 == 0 && aligned(in, 8)) {
-      g = 4;
-    } else if (M > 64 && M <= 128 && M % 2 == 0 && aligned(in, 4)) {
-      g = 2;
-    } else {
-      while (64 * ng < M) ng <<= 1;
-    }
-    full = (M == 64 * g * ng);
-    err = mode == rtopk::kExact ? rtopk::launch_h16_exact(dtype, g, ng, full, a)
-                                : rtopk::launch_h16_early(dtype, g, ng, full, a);
-  } else if (M > 128 && M % 4 == 0 && aligned(in, 16)) {
-    // 128-bit loads; groups per lane rounded up to an instantiated count
-    static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
-    int ng = 32;
-    for (int cand : kNg) {
-      if (M <= 256 * cand) {
-        ng = cand;
-        break;
-      }
-    }
-    const bool full = (M == 256 * ng);
-    err = mode == rtopk::kExact   ? rtopk::launch_g4_exact(ng, full, u8, a)
-          : mode == rtopk::kEarly ? rtopk::launch_g4_early(ng, full, u8, a)
-                                  : rtopk::launch_g4_eps(ng, full, a);
-  } else if (M > 64 && M <= 128 && M % 2 == 0 && aligned(in, 8)) {
-    err = rtopk::launch_small(2, 1, M == 128, mode, u8, a);
-  } else {
-    int ng = 1;
-    while (64 * ng < M) ng <<= 1;
-    err = rtopk::launch_small(1, ng, M == 64 * ng, mode, u8, a);
+  switch (sh.family) {
+    case rtopk::kFamBlock:
+      err = dtype != rtopk::kF32 ? rtopk::launch_block_h16(dtype, sh.g, sh.ng, sh.w, mode, a)
+            : plain              ? rtopk::launch_block_plain(sh.g, sh.ng, sh.w, mode, a)
+                                 : rtopk::launch_block_variant(sh.g, sh.ng, sh.w, mode, smallest, a);
+      break;
+    case rtopk::kFamH16:
+      err = mode == rtopk::kExact ? rtopk::launch_h16_exact(dtype, sh.g, sh.ng, sh.full, a)
+                                  : rtopk::launch_h16_early(dtype, sh.g, sh.ng, sh.full, a);
+      break;
+    case rtopk::kFamG4:
+      err = mode == rtopk::kExact   ? rtopk::launch_g4_exact(sh.ng, sh.full, u8, a)
+            : mode == rtopk::kEarly ? rtopk::launch_g4_early(sh.ng, sh.full, u8, a)
+                                    : rtopk::launch_g4_eps(sh.ng, sh.full, a);
+      break;
+    default:
+      err = rtopk::launch_small(sh.g, sh.ng, sh.full, mode, u8, a);
+      break;
   }
+  return err == hipSuccess ? RTOPK_OK : RTOPK_ERR_LAUNCH;
+}
+
+// Shared body of the backward entry points.  dense = the [N][M] array (output of the scatter, input of
+// the gather), pairs = the [N][k] gradient array (input of the scatter, output of the gather).
+int run_backward(bool gather, const float* dense, const float* pairs, const void* idx, bool u8, int64_t N, int32_t M,
+                 int32_t k, void* stream) {
+  if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
+  if (M > rtopk::kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > rtopk::kBackwardRowsM && N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row
+  if (N == 0) return RTOPK_OK;
+  if (!dense || !pairs || !idx) return RTOPK_ERR_NULL_POINTER;
+  if (!aligned(dense, 4) || !aligned(pairs, 4) || (!u8 && !aligned(idx, 4))) return RTOPK_ERR_MISALIGNED;
+  const uint64_t n_d = (uint64_t)N * (uint64_t)M * 4, n_p = (uint64_t)N * (uint64_t)k * 4;
+  const uint64_t n_i = (uint64_t)N * (uint64_t)k * (u8 ? 1 : 4);
+  if (rtopk::ranges_overlap(addr(dense), n_d, addr(pairs), n_p) || rtopk::ranges_overlap(addr(dense), n_d, addr(idx), n_i) ||
+      (gather && rtopk::ranges_overlap(addr(pairs), n_p, addr(idx), n_i)))
+    return RTOPK_ERR_OVERLAP;
+  const bool vec = M % 4 == 0 && aligned(dense, 16);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const hipError_t err = gather ? rtopk::launch_maxk_backward_gather(dense, idx, u8, N, M, k, const_cast<float*>(pairs), vec, s)
+                                : rtopk::launch_maxk_backward(pairs, idx, u8, N, M, k, const_cast<float*>(dense), vec, s);
   return err == hipSuccess ? RTOPK_OK : RTOPK_ERR_LAUNCH;
 }
 
@@ -183,10 +174,13 @@ int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k
 
 int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out, void* stream) {
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
-  if (M > kMaxM) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > rtopk::kMaxM) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > rtopk::kMaxWaveM && N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row
   if (N == 0) return RTOPK_OK;
   if (!in || !out) return RTOPK_ERR_NULL_POINTER;
   if (!aligned(in, 4) || !aligned(out, 4)) return RTOPK_ERR_MISALIGNED;
+  const uint64_t bytes = (uint64_t)N * (uint64_t)M * 4;
+  if (rtopk::ranges_overlap(addr(in), bytes, addr(out), bytes)) return RTOPK_ERR_OVERLAP;
   int mode = max_iter < 0 ? rtopk::kExact : rtopk::kEarly;
   if (mode == rtopk::kExact && k == M) {  // everything is kept: no search needed
     mode = rtopk::kEarly;
@@ -197,40 +191,37 @@ int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t m
   a.N = N;
   a.M = M;
   a.k = k;
-  a.max_iter = max_iter < 0 ? 0 : max_iter;
+  a.max_iter = max_iter < 0 ? 0 : (max_iter > rtopk::kMaxIterClamp ? rtopk::kMaxIterClamp : max_iter);
   a.out_vals = out;
   a.stream = static_cast<hipStream_t>(stream);
-  int g = 1, ng = 1;
-  if (M > kMaxWaveM) {
-    if (N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row
-    int w = 16;
-    ng = 16;
-    if (M % 4 == 0 && aligned(in, 16) && aligned(out, 16)) {
-      g = 4;
-      w = M <= 16384 ? 4 : (M <= 32768 ? 8 : 16);
-    } else {
-      while (1024 * ng < M) ng <<= 1;
-    }
-    const hipError_t e = rtopk::launch_block_dense(g, ng, w, mode, a);
-    return e == hipSuccess ? RTOPK_OK : RTOPK_ERR_LAUNCH;
-  }
-  if (M > 128 && M % 4 == 0 && aligned(in, 16) && aligned(out, 16)) {
-    static const int kNg[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
-    g = 4;
-    ng = 32;
-    for (int cand : kNg) {
-      if (M <= 256 * cand) {
-        ng = cand;
-        break;
-      }
-    }
-  } else if (M > 64 && M <= 128 && M % 2 == 0 && aligned(in, 8) && aligned(out, 8)) {
-    g = 2;
+  const rtopk::Shape sh = rtopk::classify_dense(M, addr(in), addr(out));
+  hipError_t err;
+  if (sh.family == rtopk::kFamBlock) {
+    err = rtopk::launch_block_dense(sh.g, sh.ng, sh.w, mode, a);
   } else {
-    while (64 * ng < M) ng <<= 1;
+    err = rtopk::launch_dense_any(sh.g, sh.ng, sh.full, mode, a);
   }
-  const hipError_t err = rtopk::launch_dense_any(g, ng, M == 64 * g * ng, mode, a);
   return err == hipSuccess ? RTOPK_OK : RTOPK_ERR_LAUNCH;
+}
+
+int rtopk_maxk_backward(const float* grad_vals, const int32_t* idx, int64_t N, int32_t M, int32_t k, float* grad_in,
+                        void* stream) {
+  return run_backward(false, grad_in, grad_vals, idx, false, N, M, k, stream);
+}
+
+int rtopk_maxk_backward_u8(const float* grad_vals, const uint8_t* idx, int64_t N, int32_t M, int32_t k, float* grad_in,
+                           void* stream) {
+  return run_backward(false, grad_in, grad_vals, idx, true, N, M, k, stream);
+}
+
+int rtopk_maxk_backward_gather(const float* grad_out, const int32_t* idx, int64_t N, int32_t M, int32_t k,
+                               float* grad_vals, void* stream) {
+  return run_backward(true, grad_out, grad_vals, idx, false, N, M, k, stream);
+}
+
+int rtopk_maxk_backward_gather_u8(const float* grad_out, const uint8_t* idx, int64_t N, int32_t M, int32_t k,
+                                  float* grad_vals, void* stream) {
+  return run_backward(true, grad_out, grad_vals, idx, true, N, M, k, stream);
 }
 
 const char* rtopk_status_string(int status) {
@@ -243,12 +234,13 @@ const char* rtopk_status_string(int status) {
     case RTOPK_ERR_MISALIGNED: return "pointer not aligned to its element size";
     case RTOPK_ERR_LAUNCH: return "the HIP runtime refused the launch";
     case RTOPK_ERR_BAD_EPSILON: return "eps_rel must be >= 0";
+    case RTOPK_ERR_OVERLAP: return "input and output buffers overlap";
     default: return "unknown status";
   }
 }
 
 int rtopk_version(void) { return kVersion; }
 
-int rtopk_max_m(void) { return kMaxM; }
+int rtopk_max_m(void) { return rtopk::kMaxM; }
 
 }  // extern "C"

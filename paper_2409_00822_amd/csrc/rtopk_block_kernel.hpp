@@ -42,30 +42,31 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
   return v;
 }
 
-// In the lanes whose bit is set in `mask`: the 32-bit (or, for 16-bit rows, the narrowed 16-bit) value
-// goes to vals + off_v bytes and the column to cols + off_c bytes.  Both bases are wave-uniform; the
-// kernel's control flow is uniform over the wavefront, so EXEC is all ones on entry and restored so.
+// In the lanes whose bit is set in `mask` (a subset of the active lanes): the 32-bit (or, for 16-bit
+// rows, the narrowed 16-bit) value goes to vals + off_v bytes and the column to cols + off_c bytes.  Both
+// bases are wave-uniform.  The set of active lanes is saved and put back.
 template <int DT>
 __device__ __forceinline__ void store_pair_masked(uint64_t mask, void* vals, uint32_t off_v, uint32_t value_bits,
                                                   int32_t* cols, uint32_t off_c, int32_t col) {
+  uint64_t saved;
   if constexpr (DT == kF32) {
     asm volatile(
-        "s_mov_b64 exec, %0\n\t"
-        "global_store_dword %1, %2, %3\n\t"
-        "global_store_dword %4, %5, %6\n\t"
-        "s_mov_b64 exec, -1"
-        :
+        "s_and_saveexec_b64 %0, %1\n\t"
+        "global_store_dword %2, %3, %4\n\t"
+        "global_store_dword %5, %6, %7\n\t"
+        "s_mov_b64 exec, %0"
+        : "=&s"(saved)
         : "s"(mask), "v"(off_v), "v"(value_bits), "s"(vals), "v"(off_c), "v"(col), "s"(cols)
-        : "memory");
+        : "memory", "scc");
   } else {
     asm volatile(
-        "s_mov_b64 exec, %0\n\t"
-        "global_store_short %1, %2, %3\n\t"
-        "global_store_dword %4, %5, %6\n\t"
-        "s_mov_b64 exec, -1"
-        :
+        "s_and_saveexec_b64 %0, %1\n\t"
+        "global_store_short %2, %3, %4\n\t"
+        "global_store_dword %5, %6, %7\n\t"
+        "s_mov_b64 exec, %0"
+        : "=&s"(saved)
         : "s"(mask), "v"(off_v), "v"(value_bits), "s"(vals), "v"(off_c), "v"(col), "s"(cols)
-        : "memory");
+        : "memory", "scc");
   }
 }
 
@@ -413,10 +414,9 @@ __global__ void __launch_bounds__(W * kWave)
 template <int G, int NG, int W, int MODE, bool NEG = false, int DT = kF32, bool DENSE = false>
 hipError_t launch_block(const LaunchArgs& a) {
   if (a.N > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((rtopk_block_kernel<G, NG, W, MODE, NEG, DT, DENSE>), dim3((unsigned)a.N), dim3(W * kWave), 0,
-                     a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
-                     static_cast<int32_t*>(a.out_idx), a.out_iters);
-  return hipGetLastError();
+  return launch_kernel(rtopk_block_kernel<G, NG, W, MODE, NEG, DT, DENSE>, dim3((unsigned)a.N), dim3(W * kWave), 0,
+                       a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
+                       static_cast<int32_t*>(a.out_idx), a.out_iters);
 }
 
 }  // namespace rtopk

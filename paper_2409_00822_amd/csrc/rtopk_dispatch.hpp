@@ -5,21 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "rtopk_shape.hpp"
+
 namespace rtopk {
-
-// Which algorithm of the paper (Section 3.1) a kernel instance runs.
-enum Mode : int {
-  kEarly = 0,  // Algorithm 2: max_iter steps, one-pass selection against min
-  kExact = 1,  // Algorithm 1 at epsilon = 0
-  kEps = 2     // Algorithm 1 with epsilon = eps_rel * |max|, optional exit-iteration output
-};
-
-// Element type of the input matrix and of the value output.
-enum DType : int {
-  kF32 = 0,
-  kF16 = 1,  // IEEE half
-  kBF16 = 2  // bfloat16
-};
 
 struct LaunchArgs {
   const void* in;
@@ -55,5 +43,13 @@ hipError_t launch_block_h16(int dtype, int g, int ng, int w, int mode, const Lau
 hipError_t launch_dense_any(int g, int ng, bool full, int mode, const LaunchArgs& a);
 // Narrow rows and scalar-load fallback (any M, 4-byte alignment).
 hipError_t launch_small(int g, int ng, bool full, int mode, bool u8, const LaunchArgs& a);
+
+
+// Backward edge of the MaxK non-linearity (rtopk_backward.hpp).  idx is int32_t[N][k] or, with u8,
+// uint8_t[N][k]; vec = M % 4 == 0 and the dense [N][M] array 16-byte aligned (128-bit accesses).
+hipError_t launch_maxk_backward(const float* grad_vals, const void* idx, bool u8, int64_t N, int M, int k, float* grad_in,
+                                bool vec, hipStream_t stream);
+hipError_t launch_maxk_backward_gather(const float* grad_out, const void* idx, bool u8, int64_t N, int M, int k,
+                                       float* grad_vals, bool vec, hipStream_t stream);
 
 }  // namespace rtopk

@@ -24,9 +24,9 @@ hipError_t launch_block_plain(int g, int ng, int w, int mode, const LaunchArgs& 
   }
   if (g != 1 || w != 16) return hipErrorInvalidValue;
   switch (ng) {
-    case 16: return pick<1, 16, 16>(mode, a);
-    case 32: return pick<1, 32, 16>(mode, a);
-    case 64: return pick<1, 64, 16>(mode, a);
+#define X(n) case n: return pick<1, n, 16>(mode, a);
+    RTOPK_NG_LIST_BLOCK_G1(X)
+#undef X
     default: return hipErrorInvalidValue;
   }
 }

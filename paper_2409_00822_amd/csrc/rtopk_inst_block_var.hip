@@ -25,9 +25,9 @@ hipError_t launch_block_variant(int g, int ng, int w, int mode, bool smallest, c
   }
   if (g != 1 || w != 16) return hipErrorInvalidValue;
   switch (ng) {
-    case 16: return pick<1, 16, 16>(mode, smallest, a);
-    case 32: return pick<1, 32, 16>(mode, smallest, a);
-    case 64: return pick<1, 64, 16>(mode, smallest, a);
+#define X(n) case n: return pick<1, n, 16>(mode, smallest, a);
+    RTOPK_NG_LIST_BLOCK_G1(X)
+#undef X
     default: return hipErrorInvalidValue;
   }
 }

@@ -3,9 +3,9 @@
 
 namespace rtopk {
 
-template <int NG>
-static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
-  constexpr int R = rows_per_wave(4 * NG);
+// R rows per wavefront; the column type and the k-smallest variant are picked here.
+template <int NG, int R>
+static hipError_t pick_rows(bool full, bool u8, const LaunchArgs& a) {
   if constexpr (NG == 1) {
     if (u8 && !a.smallest) return full ? launch<4, NG, R, true, kEarly, uint8_t>(a) : launch<4, NG, R, false, kEarly, uint8_t>(a);
   }
@@ -13,27 +13,23 @@ static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
     if (u8) return hipErrorInvalidValue;
     return full ? launch<4, NG, R, true, kEarly, int32_t, true>(a) : launch<4, NG, R, false, kEarly, int32_t, true>(a);
   }
-  if constexpr (R > kRowsPerWaveFew) {
-    if (a.N < kFewRows) {
-      return full ? launch<4, NG, kRowsPerWaveFew, true, kEarly, int32_t>(a)
-                  : launch<4, NG, kRowsPerWaveFew, false, kEarly, int32_t>(a);
-    }
-  }
   return full ? launch<4, NG, R, true, kEarly, int32_t>(a) : launch<4, NG, R, false, kEarly, int32_t>(a);
+}
+
+template <int NG>
+static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
+  constexpr int R = rows_per_wave(4 * NG);
+  if constexpr (R > kRowsPerWaveFew) {
+    if (a.N < kFewRows) return pick_rows<NG, kRowsPerWaveFew>(full, u8, a);  // every variant, not only int32 columns
+  }
+  return pick_rows<NG, R>(full, u8, a);
 }
 
 hipError_t launch_g4_early(int ng, bool full, bool u8, const LaunchArgs& a) {
   switch (ng) {
-    case 1: return pick<1>(full, u8, a);
-    case 2: return pick<2>(full, u8, a);
-    case 3: return pick<3>(full, u8, a);
-    case 4: return pick<4>(full, u8, a);
-    case 6: return pick<6>(full, u8, a);
-    case 8: return pick<8>(full, u8, a);
-    case 12: return pick<12>(full, u8, a);
-    case 16: return pick<16>(full, u8, a);
-    case 24: return pick<24>(full, u8, a);
-    case 32: return pick<32>(full, u8, a);
+#define X(n) case n: return pick<n>(full, u8, a);
+    RTOPK_NG_LIST_G4(X)
+#undef X
     default: return hipErrorInvalidValue;
   }
 }

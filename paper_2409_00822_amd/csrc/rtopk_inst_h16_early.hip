@@ -6,6 +6,12 @@ namespace rtopk {
 template <int DT, int G, int NG>
 static hipError_t pick(bool full, const LaunchArgs& a) {
   constexpr int R = rows_per_wave(G * NG);
+  if constexpr (R > kRowsPerWaveFew && G > 1) {
+    if (a.N < kFewRows) {
+      return full ? launch<G, NG, kRowsPerWaveFew, true, kEarly, int32_t, false, DT>(a)
+                  : launch<G, NG, kRowsPerWaveFew, false, kEarly, int32_t, false, DT>(a);
+    }
+  }
   return full ? launch<G, NG, R, true, kEarly, int32_t, false, DT>(a) : launch<G, NG, R, false, kEarly, int32_t, false, DT>(a);
 }
 
@@ -13,14 +19,9 @@ template <int DT>
 static hipError_t pick_shape(int g, int ng, bool full, const LaunchArgs& a) {
   if (g == 8) {
     switch (ng) {
-      case 1: return pick<DT, 8, 1>(full, a);
-      case 2: return pick<DT, 8, 2>(full, a);
-      case 3: return pick<DT, 8, 3>(full, a);
-      case 4: return pick<DT, 8, 4>(full, a);
-      case 6: return pick<DT, 8, 6>(full, a);
-      case 8: return pick<DT, 8, 8>(full, a);
-      case 12: return pick<DT, 8, 12>(full, a);
-      case 16: return pick<DT, 8, 16>(full, a);
+#define X(n) case n: return pick<DT, 8, n>(full, a);
+      RTOPK_NG_LIST_H8(X)
+#undef X
       default: return hipErrorInvalidValue;
     }
   }
@@ -28,14 +29,9 @@ static hipError_t pick_shape(int g, int ng, bool full, const LaunchArgs& a) {
   if (g == 2 && ng == 1) return pick<DT, 2, 1>(full, a);
   if (g != 1) return hipErrorInvalidValue;
   switch (ng) {
-    case 1: return pick<DT, 1, 1>(full, a);
-    case 2: return pick<DT, 1, 2>(full, a);
-    case 4: return pick<DT, 1, 4>(full, a);
-    case 8: return pick<DT, 1, 8>(full, a);
-    case 16: return pick<DT, 1, 16>(full, a);
-    case 32: return pick<DT, 1, 32>(full, a);
-    case 64: return pick<DT, 1, 64>(full, a);
-    case 128: return pick<DT, 1, 128>(full, a);
+#define X(n) case n: return pick<DT, 1, n>(full, a);
+    RTOPK_NG_LIST_G1(X)
+#undef X
     default: return hipErrorInvalidValue;
   }
 }

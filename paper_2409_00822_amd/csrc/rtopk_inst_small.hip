@@ -4,9 +4,9 @@
 
 namespace rtopk {
 
-template <int G, int NG, int MODE>
-static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
-  constexpr int R = rows_per_wave(G * NG);
+// R rows per wavefront; the column type and the k-smallest variant are picked here.
+template <int G, int NG, int R, int MODE>
+static hipError_t pick_rows(bool full, bool u8, const LaunchArgs& a) {
   if constexpr (64 * G * NG <= 256 && MODE != kEps) {
     if (u8 && !a.smallest) return full ? launch<G, NG, R, true, MODE, uint8_t>(a) : launch<G, NG, R, false, MODE, uint8_t>(a);
   }
@@ -16,13 +16,16 @@ static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
       return full ? launch<G, NG, R, true, MODE, int32_t, true>(a) : launch<G, NG, R, false, MODE, int32_t, true>(a);
     }
   }
-  if constexpr (R > kRowsPerWaveFew && G == 2) {
-    if (a.N < kFewRows) {
-      return full ? launch<G, NG, kRowsPerWaveFew, true, MODE, int32_t>(a)
-                  : launch<G, NG, kRowsPerWaveFew, false, MODE, int32_t>(a);
-    }
-  }
   return full ? launch<G, NG, R, true, MODE, int32_t>(a) : launch<G, NG, R, false, MODE, int32_t>(a);
+}
+
+template <int G, int NG, int MODE>
+static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
+  constexpr int R = rows_per_wave(G * NG);
+  if constexpr (R > kRowsPerWaveFew && G == 2) {
+    if (a.N < kFewRows) return pick_rows<G, NG, kRowsPerWaveFew, MODE>(full, u8, a);
+  }
+  return pick_rows<G, NG, R, MODE>(full, u8, a);
 }
 
 template <int MODE>
@@ -30,14 +33,9 @@ static hipError_t pick_mode(int g, int ng, bool full, bool u8, const LaunchArgs&
   if (g == 2 && ng == 1) return pick<2, 1, MODE>(full, u8, a);
   if (g != 1) return hipErrorInvalidValue;
   switch (ng) {
-    case 1: return pick<1, 1, MODE>(full, u8, a);
-    case 2: return pick<1, 2, MODE>(full, u8, a);
-    case 4: return pick<1, 4, MODE>(full, u8, a);
-    case 8: return pick<1, 8, MODE>(full, u8, a);
-    case 16: return pick<1, 16, MODE>(full, u8, a);
-    case 32: return pick<1, 32, MODE>(full, u8, a);
-    case 64: return pick<1, 64, MODE>(full, u8, a);
-    case 128: return pick<1, 128, MODE>(full, u8, a);
+#define X(n) case n: return pick<1, n, MODE>(full, u8, a);
+    RTOPK_NG_LIST_G1(X)
+#undef X
     default: return hipErrorInvalidValue;
   }
 }

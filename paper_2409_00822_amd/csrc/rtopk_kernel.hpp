@@ -38,6 +38,20 @@ constexpr int kWave = 64;
 #define RTOPK_WAVES_PER_BLOCK 1
 #endif
 
+// Host side: enqueue `kernel` and return the status of THIS launch.  The runtime's per-thread "last error"
+// is neither read nor cleared, so an error left behind by the caller's own earlier HIP calls is not
+// reported as a failure of the library, and stays visible to the caller.
+template <typename T>
+struct same_type {
+  using type = T;
+};
+template <typename... KArgs>
+hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                         typename same_type<KArgs>::type... args) {
+  void* ptrs[] = {static_cast<void*>(&args)...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, stream);
+}
+
 // ---- cross-lane helpers ---------------------------------------------------------------------------
 
 // v_max_f32 with optional source negation, written as asm so that no NaN-quieting canonicalisation
@@ -103,8 +117,9 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask, uint32_t add) {
 }
 
 // The search key of a value: the value itself when the k largest are wanted, its negation when the
-// k smallest are (Section 3: "largest (or smallest) ... without loss of generality").  The negation
-// folds into the source modifiers of the compares, so the smallest-k variant costs nothing extra.
+// k smallest are (Section 3 states the problem for either end of the order and develops the largest).
+// The negation folds into the source modifiers of the compares, so the smallest-k variant costs nothing
+// extra.
 template <bool NEG>
 __device__ __forceinline__ float keyof(float v) {
   return NEG ? -v : v;
@@ -117,35 +132,39 @@ __device__ __forceinline__ uint32_t add_mask_bit(uint32_t p, uint64_t mask) {
   return r;
 }
 
-// In the lanes whose bit is set in `mask`: LDS[addr] = a, LDS[addr + 4] = b.  The kernel runs with
-// all 64 lanes active whenever this is called, so EXEC is restored to all ones.
+// In the lanes whose bit is set in `mask`: LDS[addr] = a, LDS[addr + 4] = b.  `mask` must be a subset of
+// the lanes active at the call (every mask here comes from a ballot, which is); the set of active lanes
+// is saved and put back, so the block is also correct under divergent control flow.
 __device__ __forceinline__ void lds_store_pair_masked(uint64_t mask, uint32_t addr, uint32_t a, uint32_t b) {
+  uint64_t saved;
   asm volatile(
-      "s_mov_b64 exec, %0\n\t"
-      "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
-      "s_mov_b64 exec, -1"
-      :
+      "s_and_saveexec_b64 %0, %1\n\t"
+      "ds_write2_b32 %2, %3, %4 offset1:1\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved)
       : "s"(mask), "v"(addr), "v"(a), "v"(b)
-      : "memory");
+      : "memory", "scc");
 }
 
-// The same for four elements at once (one EXEC restore instead of four).
+// The same for four elements at once (the active lanes are saved and restored once for the four).
 __device__ __forceinline__ void lds_store_pairs_masked4(const uint64_t (&mk)[4], const uint32_t (&addr)[4],
                                                         const float (&a)[4], const uint32_t (&b)[4]) {
+  uint64_t saved;
   asm volatile(
-      "s_mov_b64 exec, %0\n\t"
-      "ds_write2_b32 %4, %8, %12 offset1:1\n\t"
-      "s_mov_b64 exec, %1\n\t"
-      "ds_write2_b32 %5, %9, %13 offset1:1\n\t"
-      "s_mov_b64 exec, %2\n\t"
-      "ds_write2_b32 %6, %10, %14 offset1:1\n\t"
-      "s_mov_b64 exec, %3\n\t"
-      "ds_write2_b32 %7, %11, %15 offset1:1\n\t"
-      "s_mov_b64 exec, -1"
-      :
-      : "s"(mk[0]), "s"(mk[1]), "s"(mk[2]), "s"(mk[3]), "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3]),
-        "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(b[0]), "v"(b[1]), "v"(b[2]), "v"(b[3])
-      : "memory");
+      "s_and_saveexec_b64 %[sv], %[m0]\n\t"
+      "ds_write2_b32 %[a0], %[v0], %[c0] offset1:1\n\t"
+      "s_mov_b64 exec, %[m1]\n\t"
+      "ds_write2_b32 %[a1], %[v1], %[c1] offset1:1\n\t"
+      "s_mov_b64 exec, %[m2]\n\t"
+      "ds_write2_b32 %[a2], %[v2], %[c2] offset1:1\n\t"
+      "s_mov_b64 exec, %[m3]\n\t"
+      "ds_write2_b32 %[a3], %[v3], %[c3] offset1:1\n\t"
+      "s_mov_b64 exec, %[sv]"
+      : [sv] "=&s"(saved)
+      : [m0] "s"(mk[0]), [m1] "s"(mk[1]), [m2] "s"(mk[2]), [m3] "s"(mk[3]), [a0] "v"(addr[0]), [a1] "v"(addr[1]),
+        [a2] "v"(addr[2]), [a3] "v"(addr[3]), [v0] "v"(a[0]), [v1] "v"(a[1]), [v2] "v"(a[2]), [v3] "v"(a[3]),
+        [c0] "v"(b[0]), [c1] "v"(b[1]), [c2] "v"(b[2]), [c3] "v"(b[3])
+      : "memory", "scc");
 }
 
 // if (cnt < k) hi = t; else lo = t;   (all operands wave-uniform)
@@ -441,15 +460,16 @@ __device__ __forceinline__ float midpoint_exact(float lo, float hi) {
   }
 }
 
-// In the lanes whose bit is set in `mask`: LDS[addr] = v (EXEC restored to all ones, as above).
+// In the lanes whose bit is set in `mask` (a subset of the active lanes): LDS[addr] = v.
 __device__ __forceinline__ void lds_store_masked(uint64_t mask, uint32_t addr, float v) {
+  uint64_t saved;
   asm volatile(
-      "s_mov_b64 exec, %0\n\t"
-      "ds_write_b32 %1, %2\n\t"
-      "s_mov_b64 exec, -1"
-      :
+      "s_and_saveexec_b64 %0, %1\n\t"
+      "ds_write_b32 %2, %3\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved)
       : "s"(mask), "v"(addr), "v"(v)
-      : "memory");
+      : "memory", "scc");
 }
 
 // Narrowing of a wide row's search.  A threshold between lo and hi separates only the elements whose
@@ -858,16 +878,21 @@ __device__ __forceinline__ void load_group(const typename std::conditional<DT ==
   }
 }
 
-// Cache-policy bits of the output stores.  Swept at k = 64 and 96 on M = 256 and M = 2048: "sc1" is
-// best or within 2 % of the best everywhere; "nt" is up to 5 % faster at M = 256 with many writes but
-// 12 % slower at k = 32 and 5 % slower at M = 2048; none and "sc0" are 2-10 % slower.
+// Cache-policy bits of the output stores: non-temporal.  What decides is whether a launch's outputs were
+// written before.  Timed over buffers that are rewritten in place launch after launch, and only while
+// those outputs fit the 256 MB last-level cache, cached ("sc1", "sc0 sc1") stores look best (2^20 x 256,
+// k = 32: 204 us against 216 us), because part of the write traffic is absorbed by that cache and never
+// reaches HBM; rotating the launches over distinct output buffers -- what a caller inside a larger
+// program sees -- takes that away (229 us), while non-temporal stores run the same either way (221 us).
+// Over distinct buffers "nt" is the fastest or within 0.5 % of it on every workload measured (k = 16:
+// 186 against 196 us; k = 64: 256 against 266 us; 2.4M x 256 with byte columns: 452 against 454 us; the
+// dense form: 344 against 349 us); no policy bit at all is 1-6 % slower than either.
 #ifndef RTOPK_STORE_POLICY
-#define RTOPK_STORE_POLICY "sc1"
+#define RTOPK_STORE_POLICY "nt"
 #endif
 
-// 128-bit and 32-bit output stores with the sc1 cache-policy bit (write through at device scope):
-// the outputs are written once and never read back by this kernel; on a streaming probe with this
-// kernel's traffic sc1 stores were ~2 % faster than default ones (non-temporal stores were 12 % slower).
+// 128-bit, 64-bit and 32-bit output stores with that policy: the outputs are written once and never read
+// back by this kernel.
 __device__ __forceinline__ void store_streaming(uint4* p, uint4 v) {
   typedef uint32_t u4 __attribute__((ext_vector_type(4)));
   const u4 d = {v.x, v.y, v.z, v.w};
@@ -1051,10 +1076,9 @@ hipError_t launch_dense(const LaunchArgs& a) {
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
   const size_t lds = narrows(G * NG, MODE) ? (size_t)waves * band_regs(G * NG) * kWave * sizeof(float) : 0;
-  hipLaunchKernelGGL((rtopk_dense_kernel<G, NG, R, FULL, MODE>), dim3((unsigned)blocks), dim3(waves * kWave), lds,
-                     a.stream, static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter,
-                     static_cast<float*>(a.out_vals));
-  return hipGetLastError();
+  return launch_kernel(rtopk_dense_kernel<G, NG, R, FULL, MODE>, dim3((unsigned)blocks), dim3(waves * kWave), lds,
+                       a.stream, static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter,
+                       static_cast<float*>(a.out_vals));
 }
 
 // ---- host-side launcher -------------------------------------------------------------------------------
@@ -1073,10 +1097,9 @@ hipError_t launch(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((rtopk_wave_kernel<G, NG, R, FULL, MODE, NEG, IdxT, DT>), dim3((unsigned)blocks), dim3(waves * kWave),
-                     per_wave * waves, a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
-                     static_cast<IdxT*>(a.out_idx), a.out_iters, a.vec_store);
-  return hipGetLastError();
+  return launch_kernel(rtopk_wave_kernel<G, NG, R, FULL, MODE, NEG, IdxT, DT>, dim3((unsigned)blocks),
+                       dim3(waves * kWave), per_wave * waves, a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel,
+                       a.out_vals, static_cast<IdxT*>(a.out_idx), a.out_iters, a.vec_store);
 }
 
 // Rows per wavefront for E = G*NG registers per row, from sweeps at 2^20 rows: 16 for M <= 128,

@@ -48,6 +48,10 @@ def load_library() -> ctypes.CDLL:
                    lib.rtopk_rowwise_eps, lib.rtopk_rowwise_smallest, lib.rtopk_rowwise_exact_smallest,
                    lib.rtopk_version, lib.rtopk_max_m):
             fn.restype = ctypes.c_int
+        for name in ("rtopk_maxk_backward", "rtopk_maxk_backward_u8", "rtopk_maxk_backward_gather",
+                     "rtopk_maxk_backward_gather_u8"):
+            getattr(lib, name).argtypes = [vp, vp, i64, i32, i32, vp, vp]
+            getattr(lib, name).restype = ctypes.c_int
         lib.rtopk_status_string.argtypes = [ctypes.c_int]
         lib.rtopk_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -220,3 +224,55 @@ def rtopk_maxk_dense(x, k: int, max_iter: int = -1, out=None):
     stream = torch.cuda.current_stream(x.device).cuda_stream
     _check(load_library().rtopk_maxk_dense(x.data_ptr(), N, M, k, max_iter, out.data_ptr(), stream))
     return out
+
+
+def _backward_args(idx, M: int):
+    import torch
+
+    if not (idx.is_cuda and idx.dim() == 2 and idx.is_contiguous() and idx.dtype in (torch.int32, torch.uint8)):
+        raise ValueError("idx must be a contiguous [N, k] int32 or uint8 GPU tensor")
+    if idx.dtype == torch.uint8 and M > 256:
+        raise ValueError("uint8 columns need M <= 256")
+    return idx.dtype == torch.uint8, torch.cuda.current_stream(idx.device).cuda_stream
+
+
+def rtopk_maxk_backward(grad_vals, idx, M: int, grad_in=None):
+    """Backward of the MaxK non-linearity, scatter form: gradients of the k kept values [N, k] and the
+    saved columns [N, k] (int32 or uint8) -> gradient of the dense row [N, M], zero elsewhere."""
+    import torch
+
+    u8, stream = _backward_args(idx, M)
+    N, k = idx.shape
+    if not (grad_vals.is_cuda and grad_vals.dtype == torch.float32 and grad_vals.is_contiguous()
+            and tuple(grad_vals.shape) == (N, k)):
+        raise ValueError("grad_vals must be a contiguous [N, k] float32 GPU tensor")
+    if grad_in is None:
+        grad_in = torch.empty((N, M), dtype=torch.float32, device=idx.device)
+    if not (grad_in.is_cuda and grad_in.dtype == torch.float32 and grad_in.is_contiguous()
+            and tuple(grad_in.shape) == (N, M)):
+        raise ValueError("grad_in must be a contiguous [N, M] float32 GPU tensor")
+    fn = load_library().rtopk_maxk_backward_u8 if u8 else load_library().rtopk_maxk_backward
+    _check(fn(grad_vals.data_ptr(), idx.data_ptr(), N, M, k, grad_in.data_ptr(), stream))
+    return grad_in
+
+
+def rtopk_maxk_backward_gather(grad_out, idx, grad_vals=None):
+    """Backward of the MaxK non-linearity, gather form: dense gradient rows [N, M] and the saved columns
+    [N, k] (int32 or uint8) -> the gradient entries at those columns [N, k]."""
+    import torch
+
+    if not (grad_out.is_cuda and grad_out.dtype == torch.float32 and grad_out.dim() == 2 and grad_out.is_contiguous()):
+        raise ValueError("grad_out must be a contiguous [N, M] float32 GPU tensor")
+    N, M = grad_out.shape
+    u8, stream = _backward_args(idx, M)
+    if idx.shape[0] != N:
+        raise ValueError("idx must have one row per row of grad_out")
+    k = idx.shape[1]
+    if grad_vals is None:
+        grad_vals = torch.empty((N, k), dtype=torch.float32, device=idx.device)
+    if not (grad_vals.is_cuda and grad_vals.dtype == torch.float32 and grad_vals.is_contiguous()
+            and tuple(grad_vals.shape) == (N, k)):
+        raise ValueError("grad_vals must be a contiguous [N, k] float32 GPU tensor")
+    fn = load_library().rtopk_maxk_backward_gather_u8 if u8 else load_library().rtopk_maxk_backward_gather
+    _check(fn(grad_out.data_ptr(), idx.data_ptr(), N, M, k, grad_vals.data_ptr(), stream))
+    return grad_vals

@@ -65,6 +65,7 @@ SHAPES = [
     (259, 1024, (128, 1000)), (33, 1500, (200,)), (67, 2048, (256,)), (35, 3000, (64,)),
     (70, 4096, (64, 256, 1024)), (9, 4095, (7, 512)), (17, 1021, (17,)), (21, 6000, (300,)),
     (20, 8192, (64, 512, 4097)), (7, 5001, (33,)), (5, 8191, (8,)),
+    (6, 8192, (8191, 8192)),  # the largest staging area: 8192 pairs = 64 KiB of LDS
 ]
 
 
@@ -759,3 +760,75 @@ def test_results_do_not_depend_on_the_run_or_on_what_the_outputs_held():
             torch.cuda.synchronize()
             assert torch.equal(i, i0) and torch.equal(v.view(torch.int32), v0.view(torch.int32))
             assert torch.equal(d.view(torch.int32), d0.view(torch.int32))
+
+
+def test_huge_max_iter_means_no_early_stop_and_terminates():
+    # max_iter above 512 runs as 512 (further steps cannot move a bound: shown on the CPU in
+    # test_alg2_is_a_fixed_point_after_at_most_512_steps), so INT32_MAX is a legal way to say "no early
+    # stop" even on rows whose k-th place is tied and never count exactly k.
+    R = _gpu()
+    big = 2 ** 31 - 1
+    for x, ks in ((workloads.from_pool(2000, 24, seed=1400), (1, 3, 12)), (workloads.normal_ties(3000, 256, seed=1402, p=0.5), (32,)),
+                  (workloads.small_ints(50, 4096, seed=1404, span=3), (100,)), (workloads.small_ints(6, 20000, seed=1405, span=3), (500,))):
+        for k in ks:
+            ov, oi = oracle.topk_earlystop(x, k, 600)
+            gv, gi = run_gpu(R, x, k, "early", big)
+            assert np.array_equal(gi, oi) and np.array_equal(bits(gv), bits(ov)), (x.shape, k)
+    x = workloads.normal_ties(3000, 256, seed=1406, p=0.5)
+    xd = torch.from_numpy(x).cuda()
+    d = R.rtopk_maxk_dense(xd, 32, big)
+    gv, gi = R.rtopk_rowwise_u8(xd, 32, big)
+    sv, si = R.rtopk_rowwise_smallest(xd, 32, big)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(d.cpu().numpy()), bits(oracle.maxk_dense(x, 32, 600)))
+    assert np.array_equal(gi.cpu().numpy().astype(np.int32), oracle.topk_earlystop(x, 32, 600)[1])
+    assert np.array_equal(si.cpu().numpy(), oracle.topk_earlystop_smallest(x, 32, 600)[1])
+
+
+def test_width_768_full_size():
+    # the third width of the paper's sweep (Section 4.1, Table 3): 2^18 x 768, k = 96
+    R = _gpu()
+    x = workloads.normal(1 << 18, 768, seed=768)
+    assert_parity(R, x, 96, "exact", tag="768 exact")
+    assert_parity(R, x, 96, "early", 8, tag="768 max_iter=8")
+
+
+def test_config4_eps_mode_full_size():
+    R = _gpu()
+    x = workloads.make("c4_wide")
+    assert_eps_parity(R, x, 64, 1e-4, tag="c4 eps=1e-4")
+
+
+@pytest.mark.parametrize("name,ks", [("x_wide32k", (256, 2048)), ("x_wide64k", (512,))])
+def test_workgroup_per_row_bench_workloads_full_size(name, ks):
+    # the two workloads the workgroup-per-row kernel is timed on, at the size that is timed
+    R = _gpu()
+    x = workloads.make(name)
+    for k in ks:
+        assert_parity(R, x, k, "exact", tag=f"{name} k={k} exact")
+        assert_parity(R, x, k, "early", 8, tag=f"{name} k={k} max_iter=8")
+
+
+@pytest.mark.parametrize("N", [1, 100, 4097, 32767])
+def test_few_rows_take_the_two_rows_per_wavefront_shape_in_every_variant(N):
+    # fewer than 32768 narrow rows: uint8 columns, the k smallest, the precision-bounded mode, 16-bit rows
+    # and the dense form all run the 2-rows-per-wavefront instances
+    R = _gpu()
+    for M, k in ((256, 32), (128, 16), (200, 25)):
+        x = workloads.normal_ties(N, M, seed=N + M, p=0.2)
+        assert_parity(R, x, k, "exact", u8=True, tag=f"u8 N={N} M={M}")
+        assert_parity(R, x, k, "early", 6, u8=True, tag=f"u8 N={N} M={M}")
+        assert_smallest_parity(R, x, k, "exact", tag=f"smallest N={N} M={M}")
+        assert_smallest_parity(R, x, k, "early", 6, tag=f"smallest N={N} M={M}")
+        assert_eps_parity(R, x, k, 1e-3, tag=f"eps N={N} M={M}")
+        xd = torch.from_numpy(x).cuda()
+        d = R.rtopk_maxk_dense(xd, k)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(d.cpu().numpy()), bits(oracle.maxk_dense(x, k)))
+        for kind, tdt in (("f16", torch.float16), ("bf16", torch.bfloat16)):
+            b16 = workloads.to_bits16(x, kind)
+            x16 = torch.from_numpy(b16.view(np.int16)).cuda().view(tdt)
+            gv, gi = getattr(R, "rtopk_rowwise_exact_" + kind)(x16, k)
+            torch.cuda.synchronize()
+            ov, oi = oracle.topk_exact_16(b16, kind, k)
+            assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(gv.view(torch.int16).cpu().numpy().view(np.uint16), ov)
