@@ -10,7 +10,7 @@
 // so every load instruction of a wavefront still covers 64*G*4 contiguous bytes, the W wavefronts of a
 // group step cover W KiB contiguous, and column order is (g, w, lane, c).  W is 4, 8 or 16, chosen so
 // that a lane holds up to 64 values: fewer, fatter wavefronts spread the per-step fixed cost (two
-// cross-lane sums, the LDS round trip, the barrier) over more compares, and narrower workgroups leave
+// cross-lane sums, the LDS round trip, the barrier) over more elements, and narrower workgroups leave
 // room for more rows per compute unit, whose load and search phases then overlap.
 //
 // Every wavefront evaluates the same thresholds on the same totals, so all of them take the same
@@ -23,13 +23,6 @@
 
 #include "rtopk_kernel.hpp"
 
-// Share of a lane's E values counted per lane rather than by mask popcount (see count_ge_wide): all of
-// them here -- the few wavefronts that share a SIMD run in lock step between barriers, so nothing hides
-// the compare -> scalar popcount latency (8192 x 32768: 397 -> 380 us).
-#ifndef RTOPK_BLOCK_ACC_OF
-#define RTOPK_BLOCK_ACC_OF(E) (E)
-#endif
-
 namespace rtopk {
 
 // Inclusive prefix sum over the 64 lanes of a wavefront (not on the hot path: used once per row).
@@ -40,6 +33,102 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
     if (lane >= d) v += t;
   }
   return v;
+}
+
+// Number of this lane's E keys that are below t, from the sign bits of key - t (see count_ge_wide: two
+// full-rate vector instructions per element, no scalar work).
+template <int E, bool NEG>
+__device__ __forceinline__ uint32_t lane_count_below(const float (&x)[E], float t) {
+  const float tz = (t == 0.0f) ? -0.0f : t;
+  uint32_t below = 0, pack = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const float d = keyof<NEG>(x[e]) - tz;
+    pack = __builtin_amdgcn_alignbit(pack, __float_as_uint(d), 31);  // (pack << 1) | sign(d)
+    if ((e & 31) == 31 || e + 1 == E) {
+      below += (uint32_t)__builtin_popcount(pack);
+      pack = 0;
+    }
+  }
+  return below;
+}
+
+// Sum over each row of 16 lanes; every lane of a row ends up with its row's total.
+__device__ __forceinline__ uint32_t row16_sum(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);  // row_half_mirror
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, false);  // row_mirror
+  return v;
+}
+
+// Inclusive prefix sum over the 64 lanes with six DPP steps (a lane without a source keeps 0 added).
+__device__ __forceinline__ uint32_t wave_inclusive_scan_dpp(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+typedef __attribute__((address_space(3))) float lds_float;
+constexpr uint32_t kNoRoom = 0xffffffffu;
+
+// The wavefront's members of the band lo <= key < hi go to consecutive 4-byte slots of LDS, in any order.
+// Every lane first finds its own members from the sign bits of key - lo and key - hi (four full-rate
+// vector instructions per element, no scalar work); the lanes' counts are scanned, `reserve(n, above)`
+// returns the byte address of n free slots, or kNoRoom (and is told how many keys are at or above hi); then each
+// lane walks its elements once more and stores every one of them -- members to the lane's next slot,
+// the others to a per-lane dummy word at `dummy` -- so that no lane mask or branch is needed.
+template <int E, bool NEG, typename Reserve>
+__device__ __forceinline__ void scatter_band_members(const float (&x)[E], float lo, float hi, int lane, uint32_t dummy,
+                                                     Reserve reserve) {
+  constexpr int GROUPS = (E + 31) / 32;
+  const float loz = (lo == 0.0f) ? -0.0f : lo, hiz = (hi == 0.0f) ? -0.0f : hi;
+  uint32_t member[GROUPS];
+  uint32_t n_lane = 0, above_lane = 0;
+  {
+    uint32_t pl = 0, ph = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const float key = keyof<NEG>(x[e]);
+      pl = __builtin_amdgcn_alignbit(pl, __float_as_uint(key - loz), 31);  // sign set: key < lo
+      ph = __builtin_amdgcn_alignbit(ph, __float_as_uint(key - hiz), 31);  // sign set: key < hi
+      if ((e & 31) == 31 || e + 1 == E) {
+        const int filled = (e & 31) + 1;  // element j of the group sits at bit filled - 1 - j
+        const uint32_t valid = filled == 32 ? 0xffffffffu : ((1u << filled) - 1u);
+        member[e / 32] = ~pl & ph & valid;
+        n_lane += (uint32_t)__builtin_popcount(member[e / 32]);
+        above_lane += (uint32_t)__builtin_popcount(~ph & valid);
+        pl = 0;
+        ph = 0;
+      }
+    }
+  }
+  const uint32_t incl = wave_inclusive_scan_dpp(n_lane);
+  const uint32_t n_wave = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+  const uint32_t above = (uint32_t)wave_sum((int)above_lane);
+  const uint32_t base = reserve(n_wave, above);  // wave-uniform LDS byte address, or kNoRoom
+  if (base == kNoRoom) {
+    // cannot happen on finite input (the caller has bounded the band by its counts); with NaN or
+    // infinite keys the sign bits need not agree with those counts, and then nothing is stored
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) member[g] = 0;
+  }
+  // the lane's slots are filled from its last one downwards
+  uint32_t addr = base + (incl - 1u) * 4u;
+  const uint32_t trash = dummy + (uint32_t)lane * 4u;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int filled = (e / 32 == GROUPS - 1 && E % 32 != 0) ? E % 32 : 32;
+    const int bit = filled - 1 - (e & 31);
+    const int m = ((int)(member[e / 32] << (31 - bit))) >> 31;  // -1 for a member, 0 otherwise
+    const uint32_t a = (addr & (uint32_t)m) | (trash & ~(uint32_t)m);
+    *reinterpret_cast<lds_float*>(a) = x[e];
+    addr += (uint32_t)(m * 4);  // one slot down after a member
+  }
 }
 
 // In the lanes whose bit is set in `mask` (a subset of the active lanes): the 32-bit (or, for 16-bit
@@ -70,6 +159,10 @@ __device__ __forceinline__ void store_pair_masked(uint64_t mask, void* vals, uin
   }
 }
 
+// Register budget: a row of 64 values per lane compiles to 83 registers, i.e. 5 wavefronts per SIMD and,
+// at 8 wavefronts per workgroup, two rows per compute unit.  Forcing 80 registers (a third row per
+// compute unit, at the price of 5 spilled registers) measured no faster in exact mode and 7-15 % slower
+// with early stopping, so the allocation is left to the compiler.
 template <int G, int NG, int W, int MODE, bool NEG, int DT, bool DENSE>
 __global__ void __launch_bounds__(W * kWave)
     rtopk_block_kernel(const void* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
@@ -82,10 +175,9 @@ __global__ void __launch_bounds__(W * kWave)
   __shared__ float s_hi[W], s_nlo[W];  // per-wavefront maximum and negated minimum
   __shared__ int s_cnt[2][W];          // per-wavefront counts of a search step, double buffered
   __shared__ int s_tab[2][T];          // candidates per cell of class A / class B, then their exclusive prefixes
-  // narrowing of Algorithm 1's search (see gather_band): per-wavefront gather areas, the whole row's
-  // band, its size, and what wavefront 0 hands back after finishing the search alone
-  __shared__ float s_gather[W][kBandRegs * kWave];
-  __shared__ float s_band[kBandRegs * kWave];
+  // narrowing of Algorithm 1's search (see gather_band): the whole row's band, its size, and what
+  // wavefront 0 hands back after finishing the search alone
+  __shared__ float s_band[kBandRegs * kWave + W * kWave];  // the row's band, then one dummy word per lane of the workgroup
   __shared__ int s_tot[2];  // band members / elements at or above hi, summed over the wavefronts
   __shared__ float s_res[3];
   __shared__ int s_resi[2];
@@ -145,18 +237,21 @@ __global__ void __launch_bounds__(W * kWave)
     }
   }
 
-  // cnt = #{row elements with key >= t}: this wavefront's share, then the sum over the workgroup.
-  // `step` selects the half of s_cnt that is written; one barrier per step is enough because a half is
-  // not written again before every wavefront has passed the next barrier.
-  constexpr int ACC = E <= 8 ? 0 : RTOPK_BLOCK_ACC_OF(E);
+  // cnt = #{row elements with key >= t}.  Every lane counts its keys below t, the wavefront sums them,
+  // lane 0 posts the sum, and after the barrier every wavefront adds up the W posted sums itself (they sit
+  // in one row of 16 lanes).  `step` selects the half of s_cnt that is written; one barrier per step is
+  // enough because a half is not written again before every wavefront has passed the next barrier.
+  // (Adding the lanes' counts to one LDS word with atomics instead, which saves the second reduction,
+  // measured slower: 8192 x 32768 at eight steps 252 -> 266 us.)
   int step = 0;
   auto count = [&](float t) -> int {
-    const int mine = count_ge_wide<E, ACC, NEG>(x, t);
+    const int mine = wave_sum((int)lane_count_below<E, NEG>(x, t));
     const int p = step & 1;
     ++step;
     if (lane == 0) s_cnt[p][wave] = mine;
     __syncthreads();
-    return wave_sum(lane < W ? s_cnt[p][lane] : 0);
+    const int below = __builtin_amdgcn_readfirstlane((int)row16_sum(lane < W ? (uint32_t)s_cnt[p][lane] : 0u));
+    return W * kWave * E - below;  // padded columns hold a key of -inf and are among the `below`
   };
 
   // The selection is described by two classes of elements and a limit for each:
@@ -173,6 +268,8 @@ __global__ void __launch_bounds__(W * kWave)
     float thres = lo;
     int steps = 0, cnt_lo = M, cnt_hi = 0;
     const float eps = MODE == kEps ? eps_rel * __builtin_fabsf(hi) : 0.0f;
+    // (Narrowing as soon as the band fits stays the fastest: never narrowing costs 3 % on Laplace rows --
+    // 12.3 full-width steps on average at 32768 columns -- and starting only after 8 to 14 steps 7-12 %.)
     auto fits = [&](int cnt) -> bool {  // after move_bound with this count
       cnt_lo = cnt < k ? cnt_lo : cnt;
       cnt_hi = cnt < k ? cnt : cnt_hi;
@@ -225,23 +322,18 @@ __global__ void __launch_bounds__(W * kWave)
       }
     }
     if (narrow) {  // uniform over the workgroup
-      // every wavefront gathers its own band members, then appends them to the row's band
-      float band[kBandRegs];
-      uint32_t nb;
-      const int above = gather_band<E, NEG, true>(x, lo, hi, lane, (uint32_t)(uintptr_t)s_gather[wave], band, nb);
-      // a place in the row's band for this wavefront's members (any order will do)
-      uint32_t off = 0;
-      if (lane == 0) {
-        off = (uint32_t)atomicAdd(&s_tot[0], (int)nb);
-        atomicAdd(&s_tot[1], above);
-      }
-      off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
+      // every wavefront appends its band members to the row's band (any order will do)
       const uint32_t dst = (uint32_t)(uintptr_t)s_band;
-#pragma unroll
-      for (int j = 0; j < kBandRegs; ++j) {
-        const uint32_t i = (uint32_t)lane + 64u * j;
-        lds_store_masked(__builtin_amdgcn_ballot_w64(i < nb), dst + (off + i) * 4u, band[j]);
-      }
+      scatter_band_members<E, NEG>(x, lo, hi, lane, dst + (uint32_t)((kBandRegs + wave) * kWave) * 4u,
+                                   [&](uint32_t n, uint32_t above) -> uint32_t {
+                                     uint32_t off = 0;
+                                     if (lane == 0) {
+                                       off = (uint32_t)atomicAdd(&s_tot[0], (int)n);
+                                       atomicAdd(&s_tot[1], (int)above);
+                                     }
+                                     off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
+                                     return off + n <= (uint32_t)(kBandRegs * kWave) ? dst + off * 4u : kNoRoom;
+                                   });
       __syncthreads();
       if (wave == 0) {
         float all[kBandRegs];

@@ -200,16 +200,45 @@ __device__ __forceinline__ int wave_sum(int v) {
   return __builtin_amdgcn_readlane(v, 63);
 }
 
-// The same count for wide rows, without keeping masks.  A mask popcount costs one vector and two
-// scalar instructions per 64 elements, a per-lane accumulation two vector and no scalar ones; wide
-// rows split the elements between the two so that neither unit is the bottleneck (ACC of the E
-// elements are accumulated per lane and reduced once).
+// The same count for wide rows, without keeping masks.  Two ways to count, per element:
+//   by mask popcount: one compare that writes the 64-lane mask to scalar registers, then a scalar popcount
+//     and add.  Measured issue cost on MI355X (all wavefronts of a SIMD busy): ~4.4 cycles of the vector
+//     unit per compare (a vector instruction that writes a lane mask runs at about half rate) plus two
+//     scalar instructions at ~4.8 cycles each per SIMD (the compute unit's scalar unit serves its four SIMDs
+//     in turn) -- the scalar side is the limit.
+//   per lane: d = key - t (one full-rate subtraction, ~2.5 cycles), whose sign bit says key < t, and one
+//     v_alignbit that shifts that bit into a per-lane bit pack (~2.5 cycles); every 32 elements one
+//     v_bcnt adds the pack's population to a per-lane counter, and the counters are summed over the
+//     wavefront once per step.  ~5 cycles per element and no scalar work, against ~8.4 for a compare plus
+//     an add-with-carry (both of which go through VCC and run at half rate).
+// ACC of the E elements are counted per lane, the rest by popcount.  Below 32 elements per lane the fixed
+// cost of the bit-pack form (the zero test, the final subtraction) outweighs its gain and a compare plus
+// add-with-carry per element is kept (M = 1024: 232 us against 243 us per 2^18 rows); from 32 on the
+// bit pack wins (M = 8192: 222 -> 213 us exact, 218 -> 203 us at eight steps; one workgroup per row,
+// M = 32768: 337 -> 317 us and 279 -> 252 us).
+//
+// The sign test is exact: with denormals kept, key - t is zero only when key == t, and rounding never
+// changes its sign otherwise.  Zero needs care: (-0) - (+0) = -0 would count a key of -0 as below a
+// threshold of +0, so a zero threshold is taken as -0 (then key - t = key + 0, which is +0 for either zero).
 template <int E, int ACC, bool NEG>
 __device__ __forceinline__ int count_ge_wide(const float (&x)[E], float t) {
   int cnt = 0;
 #pragma unroll
   for (int e = ACC; e < E; ++e) cnt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keyof<NEG>(x[e]) >= t));
-  if constexpr (ACC > 0) {
+  if constexpr (ACC >= 32) {
+    const float tz = (t == 0.0f) ? -0.0f : t;
+    uint32_t below = 0, pack = 0;
+#pragma unroll
+    for (int e = 0; e < ACC; ++e) {
+      const float d = keyof<NEG>(x[e]) - tz;
+      pack = __builtin_amdgcn_alignbit(pack, __float_as_uint(d), 31);  // (pack << 1) | sign(d)
+      if ((e & 31) == 31 || e + 1 == ACC) {
+        below += (uint32_t)__builtin_popcount(pack);
+        pack = 0;
+      }
+    }
+    cnt += ACC * kWave - wave_sum((int)below);
+  } else if constexpr (ACC > 0) {
     int acc = 0;
 #pragma unroll
     for (int e = 0; e < ACC; ++e) acc += (keyof<NEG>(x[e]) >= t) ? 1 : 0;
@@ -580,11 +609,12 @@ __device__ __forceinline__ void search_band(const float (&band)[BR], int above, 
   }
 }
 
-// How many of a wide row's E values per lane are counted per lane (v_cmp + v_addc, reduced once per
+// How many of a wide row's E values per lane are counted per lane (reduced over the wavefront once per
 // step) rather than by mask popcount on the scalar unit (see count_ge_wide).  From sweeps on MI355X:
-// a third up to 48 values per lane, two thirds at 64, all of them from 96 on -- the more registers a
-// wavefront holds the fewer wavefronts share a SIMD, and the less of the compare -> scalar popcount
-// latency is hidden (M = 8192: 361 -> 276 us per 32768 rows, M = 6144: 284 -> 239 us, M = 4096: 214 -> 205 us).
+// a third up to 48 values per lane, two thirds at 64, all of them from 96 on -- the scalar unit is shared
+// by the four SIMDs of a compute unit and is the first to saturate, and the more registers a wavefront
+// holds the fewer wavefronts share a SIMD to hide the compare -> scalar popcount latency
+// (M = 8192: 361 -> 276 us per 32768 rows, M = 6144: 284 -> 239 us, M = 4096: 214 -> 205 us).
 #ifndef RTOPK_ACC_OF
 #define RTOPK_ACC_OF(E) ((E) >= 96 ? (E) : ((E) >= 64 ? (2 * (E)) / 3 : ((E) - 3) / 3))
 #endif
