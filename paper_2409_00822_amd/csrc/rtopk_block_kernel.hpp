@@ -370,6 +370,9 @@ __global__ void __launch_bounds__(W * kWave)
     }
   } else {
     // Algorithm 2: max_iter steps (fewer once a step counts exactly k), then the first k of key >= lo.
+    // (Counting the midpoint and both midpoints that can follow it in one pass -- two levels per barrier,
+    // three counts per element -- gives the same bounds but measured slower, 250 -> 276 us at eight steps on
+    // 8192 x 32768: a step is bound by its counting work, not by the barrier.)
     for (int it = 0; it < max_iter; ++it) {
       const float thres = (lo + hi) * 0.5f;
       const int cnt = count(thres);

@@ -12,7 +12,7 @@ static hipError_t pick_rows(bool full, int mode, const LaunchArgs& a) {
 
 template <int G, int NG>
 static hipError_t pick(bool full, int mode, const LaunchArgs& a) {
-  constexpr int R = rows_per_wave(G * NG);
+  constexpr int R = (G == 4 && NG == 1) ? kRowsPerWaveFp32M256 : rows_per_wave(G * NG);
   if constexpr (R > kRowsPerWaveFew && G > 1) {
     if (a.N < kFewRows) return pick_rows<G, NG, kRowsPerWaveFew>(full, mode, a);
   }

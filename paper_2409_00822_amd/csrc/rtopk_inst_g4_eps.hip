@@ -5,7 +5,7 @@ namespace rtopk {
 
 template <int NG>
 static hipError_t pick(bool full, const LaunchArgs& a) {
-  constexpr int R = rows_per_wave(4 * NG);
+  constexpr int R = NG == 1 ? kRowsPerWaveFp32M256 : rows_per_wave(4 * NG);
   if constexpr (R > kRowsPerWaveFew) {
     if (a.N < kFewRows) {
       return full ? launch<4, NG, kRowsPerWaveFew, true, kEps, int32_t>(a)

@@ -22,6 +22,9 @@ static hipError_t pick(bool full, bool u8, const LaunchArgs& a) {
   if constexpr (R > kRowsPerWaveFew) {
     if (a.N < kFewRows) return pick_rows<NG, kRowsPerWaveFew>(full, u8, a);  // every variant, not only int32 columns
   }
+  if constexpr (NG == 1) {
+    if (!u8) return pick_rows<NG, kRowsPerWaveFp32M256>(full, u8, a);
+  }
   return pick_rows<NG, R>(full, u8, a);
 }
 

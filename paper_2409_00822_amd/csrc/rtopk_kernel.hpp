@@ -1135,6 +1135,13 @@ hipError_t launch(const LaunchArgs& a) {
 // Rows per wavefront for E = G*NG registers per row, from sweeps at 2^20 rows: 16 for M <= 128,
 // 8 for M = 256, 2 for M = 512..1024 (M = 512 runs 10 % slower with 4), 1 beyond.
 constexpr int rows_per_wave(int E) { return E <= 2 ? 16 : (E <= 4 ? 8 : (E <= 16 ? 2 : 1)); }
+// fp32 rows of 129..256 columns with int32 columns (and their dense form) take 4 instead: with
+// non-temporal output stores the smaller per-wavefront footprint streams better (2^20 x 256: k = 32
+// 221 -> 215 us, k = 64 254 -> 247 us, k = 128 356 -> 345 us, dense 346 -> 339 us; with no search steps at
+// all, 2 rows per wavefront reach 200 us but the search then costs 47 us more).  The variants that are
+// bound by instruction issue rather than by memory keep 8, which amortises the per-wavefront work over
+// more rows: rows stored in 16 bits (192 against 202 us) and byte-wide columns (2.4M rows: 475 against 483 us).
+constexpr int kRowsPerWaveFp32M256 = 4;
 
 // Few rows: with 8 or 16 rows per wavefront a launch of less than ~32768 rows does not even put two
 // wavefronts on every SIMD, and each of them walks its rows one after the other.  Two rows per wavefront

@@ -240,12 +240,13 @@ def test_every_expected_kernel_family_is_in_the_built_library():
     if not os.path.exists(R.lib_path()):
         pytest.skip("library not built")
     syms = subprocess.run(["nm", "-D", "--defined-only", "-C", R.lib_path()], capture_output=True, text=True).stdout
-    for needle in ("rtopk::rtopk_wave_kernel<4, 1, 8, true, 1, false, int, 0>",      # headline, exact
-                   "rtopk::rtopk_wave_kernel<4, 1, 8, true, 0, false, int, 0>",      # headline, early stop
+    for needle in ("rtopk::rtopk_wave_kernel<4, 1, 4, true, 1, false, int, 0>",      # headline, exact
+                   "rtopk::rtopk_wave_kernel<4, 1, 4, true, 0, false, int, 0>",      # headline, early stop
                    "rtopk::rtopk_wave_kernel<4, 1, 2, true, 1, false, unsigned char, 0>",  # few rows, uint8 columns
                    "rtopk::rtopk_wave_kernel<4, 16, 1, true, 1, false, int, 0>",     # M = 4096
                    "rtopk::rtopk_wave_kernel<4, 1, 8, true, 1, false, int, 2>",      # bfloat16 rows, M = 256
-                   "rtopk::rtopk_dense_kernel<4, 1, 8, true, 1>",
+                   "rtopk::rtopk_dense_kernel<4, 1, 4, true, 1>",
+                   "rtopk::rtopk_wave_kernel<4, 1, 8, true, 1, false, unsigned char, 0>",  # byte-wide columns keep 8 rows
                    "rtopk::rtopk_block_kernel<4, 16, 8, 1, false, 0, false>",        # M = 32768
                    "rtopk::maxk_scatter_rows_kernel<int, 8, true>",
                    "rtopk::maxk_gather_rows_kernel<unsigned char, 8, true>"):
