@@ -60,8 +60,9 @@ def measured_traffic(path, mode_arg=1):
     if len(found) == 1:
         return found[0][2]
     for name, args, total in found:
-        # MODE is the 5th template argument of rtopk_wave_kernel / rtopk_dense_kernel, the 4th of rtopk_block_kernel
-        pos = 3 if name == "rtopk_block_kernel" else 4
+        # MODE is the 5th template argument of rtopk_wave_kernel / rtopk_dense_kernel, the 4th of rtopk_block_kernel,
+        # the 2nd of rtopk_stream_kernel
+        pos = 3 if name == "rtopk_block_kernel" else (1 if name == "rtopk_stream_kernel" else 4)
         if len(args) > pos and args[pos] == str(mode_arg):
             return total
     return None
@@ -407,6 +408,8 @@ def main():
 
     if backward:
         kernel = ("maxk_scatter_" if args.op == "backward" else "maxk_gather_") + ("rows_kernel" if M <= 2048 else "block_kernel")
+    elif M > 65536:
+        kernel = "rtopk_stream_kernel"
     elif M > 8192:
         kernel = "rtopk_block_kernel"
     else:

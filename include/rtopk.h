@@ -28,9 +28,12 @@
  *    error nothing was enqueued.  A pending error of the caller's own earlier HIP calls is neither
  *    reported nor cleared.  Faults of the asynchronous work surface at the caller's next
  *    synchronisation, as with any HIP launch.
- *  - Limits: 1 <= k <= M <= rtopk_max_m() = 65536 (256 in the *_u8 variants); 0 <= N; N * M and N * k
- *    must fit in int64_t.  Rows wider than 8192 columns are handled by one workgroup per row, and
- *    then N < 2^31.
+ *  - Limits: 1 <= k <= M <= rtopk_max_m() = 2^24 for fp32 rows with int32 columns (65536 for rows stored
+ *    in 16 bits, the dense form and the backward edge; 256 in the *_u8 variants); 0 <= N; N * M and
+ *    N * k must fit in int64_t.  Rows wider than 8192 columns are handled by one workgroup per row, and
+ *    then N < 2^31.  Rows wider than 65536 columns are not held on chip but read several times (once for
+ *    the minimum and maximum, once per eight search steps, once to write the result), and a launch of
+ *    fewer such rows than the GPU has compute units leaves the others idle.
  */
 #ifndef RTOPK_H_
 #define RTOPK_H_
@@ -46,7 +49,7 @@ enum {
   RTOPK_ERR_NULL_POINTER = -1,  /* a data pointer is NULL while N > 0 */
   RTOPK_ERR_BAD_SHAPE = -2,     /* N < 0, M < 1, k < 1 or k > M */
   RTOPK_ERR_BAD_MAX_ITER = -3,  /* max_iter < 0 */
-  RTOPK_ERR_M_TOO_LARGE = -4,   /* M > rtopk_max_m(), or M > 256 in a *_u8 variant */
+  RTOPK_ERR_M_TOO_LARGE = -4,   /* M > rtopk_max_m(); M > 65536 for 16-bit rows, dense form, backward edge; M > 256 for *_u8 */
   RTOPK_ERR_MISALIGNED = -5,    /* a pointer is not aligned to its element size */
   RTOPK_ERR_LAUNCH = -6,        /* the HIP runtime refused the launch */
   RTOPK_ERR_BAD_EPSILON = -7,   /* eps_rel is negative or NaN */
@@ -173,7 +176,7 @@ const char* rtopk_status_string(int status);
 /* Library version, major * 10000 + minor * 100 + patch. */
 int rtopk_version(void);
 
-/* Largest supported row width M. */
+/* Largest supported row width M (fp32 rows, int32 columns). */
 int rtopk_max_m(void);
 
 #ifdef __cplusplus

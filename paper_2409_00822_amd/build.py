@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "librtopk.so")
 
 SOURCES = ["rtopk_api.hip", "rtopk_inst_g4_exact.hip", "rtopk_inst_g4_early.hip", "rtopk_inst_g4_eps.hip",
            "rtopk_inst_small.hip", "rtopk_inst_h16_exact.hip", "rtopk_inst_h16_early.hip", "rtopk_inst_dense.hip", "rtopk_inst_block.hip", "rtopk_inst_block_var.hip",
-           "rtopk_inst_block_dense.hip", "rtopk_inst_block_h16.hip", "rtopk_inst_backward.hip"]
+           "rtopk_inst_block_dense.hip", "rtopk_inst_block_h16.hip", "rtopk_inst_backward.hip", "rtopk_inst_stream.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

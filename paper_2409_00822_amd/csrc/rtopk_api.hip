@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int kVersion = 600;  // 0.6.0
+constexpr int kVersion = 700;  // 0.7.0
 
 inline uintptr_t addr(const void* p) { return reinterpret_cast<uintptr_t>(p); }
 inline bool aligned(const void* p, uintptr_t a) { return rtopk::is_aligned(addr(p), a); }
@@ -25,7 +25,7 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
   if (mode == rtopk::kEarly && max_iter < 0) return RTOPK_ERR_BAD_MAX_ITER;
   if (mode == rtopk::kEps && !(eps_rel >= 0.0f)) return RTOPK_ERR_BAD_EPSILON;
-  if (M > rtopk::kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > (dtype == rtopk::kF32 ? rtopk::kMaxM : rtopk::kMaxBlockM) || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
   if (M > rtopk::kMaxWaveM && N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row: 2^31 - 1 rows
   if (N == 0) return RTOPK_OK;
   if (!in || !out_vals || !out_idx) return RTOPK_ERR_NULL_POINTER;
@@ -69,6 +69,9 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
   const rtopk::Shape sh = rtopk::classify(M, dtype, plain, addr(in));
   hipError_t err;
   switch (sh.family) {
+    case rtopk::kFamStream:
+      err = rtopk::launch_stream_any(sh.g, mode, smallest, a);
+      break;
     case rtopk::kFamBlock:
       err = dtype != rtopk::kF32 ? rtopk::launch_block_h16(dtype, sh.g, sh.ng, sh.w, mode, a)
             : plain              ? rtopk::launch_block_plain(sh.g, sh.ng, sh.w, mode, a)
@@ -95,7 +98,7 @@ int run(const void* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float
 int run_backward(bool gather, const float* dense, const float* pairs, const void* idx, bool u8, int64_t N, int32_t M,
                  int32_t k, void* stream) {
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
-  if (M > rtopk::kMaxM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > rtopk::kMaxBlockM || (u8 && M > 256)) return RTOPK_ERR_M_TOO_LARGE;
   if (M > rtopk::kBackwardRowsM && N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row
   if (N == 0) return RTOPK_OK;
   if (!dense || !pairs || !idx) return RTOPK_ERR_NULL_POINTER;
@@ -174,7 +177,7 @@ int rtopk_rowwise_exact_bf16(const uint16_t* in, int64_t N, int32_t M, int32_t k
 
 int rtopk_maxk_dense(const float* in, int64_t N, int32_t M, int32_t k, int32_t max_iter, float* out, void* stream) {
   if (N < 0 || M < 1 || k < 1 || k > M) return RTOPK_ERR_BAD_SHAPE;
-  if (M > rtopk::kMaxM) return RTOPK_ERR_M_TOO_LARGE;
+  if (M > rtopk::kMaxBlockM) return RTOPK_ERR_M_TOO_LARGE;
   if (M > rtopk::kMaxWaveM && N > 0x7fffffffLL) return RTOPK_ERR_BAD_SHAPE;  // one workgroup per row
   if (N == 0) return RTOPK_OK;
   if (!in || !out) return RTOPK_ERR_NULL_POINTER;
@@ -230,7 +233,9 @@ const char* rtopk_status_string(int status) {
     case RTOPK_ERR_NULL_POINTER: return "null data pointer with N > 0";
     case RTOPK_ERR_BAD_SHAPE: return "bad shape: need N >= 0 and 1 <= k <= M";
     case RTOPK_ERR_BAD_MAX_ITER: return "max_iter must be >= 0";
-    case RTOPK_ERR_M_TOO_LARGE: return "M exceeds the supported row width (65536; 256 for uint8 columns)";
+    case RTOPK_ERR_M_TOO_LARGE:
+      return "M exceeds the supported row width (2^24 for fp32 rows with int32 columns; 65536 for 16-bit rows, the dense "
+             "form and the backward edge; 256 for uint8 columns)";
     case RTOPK_ERR_MISALIGNED: return "pointer not aligned to its element size";
     case RTOPK_ERR_LAUNCH: return "the HIP runtime refused the launch";
     case RTOPK_ERR_BAD_EPSILON: return "eps_rel must be >= 0";

@@ -38,6 +38,9 @@ hipError_t launch_block_plain(int g, int ng, int w, int mode, const LaunchArgs& 
 hipError_t launch_block_variant(int g, int ng, int w, int mode, bool smallest, const LaunchArgs& a);  // fp32: kEps, or the k smallest
 hipError_t launch_block_dense(int g, int ng, int w, int mode, const LaunchArgs& a);                   // fp32 dense output
 hipError_t launch_block_h16(int dtype, int g, int ng, int w, int mode, const LaunchArgs& a);          // half / bfloat16 rows
+// Rows wider than 65536 columns (fp32, int32 columns, every mode, the k largest or smallest): one
+// workgroup per row, the row streamed.  g = 4 (M % 4 == 0 and 16-byte aligned input) or 1.
+hipError_t launch_stream_any(int g, int mode, bool smallest, const LaunchArgs& a);
 // Dense-output form (fp32; a.out_vals is the [N][M] output, a.out_idx unused).  g, ng, full as above;
 // mode kEarly or kExact.
 hipError_t launch_dense_any(int g, int ng, bool full, int mode, const LaunchArgs& a);

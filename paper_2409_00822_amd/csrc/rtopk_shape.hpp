@@ -33,15 +33,17 @@ enum DType : int {
   kBF16 = 2  // bfloat16
 };
 
-constexpr int kMaxM = 65536;     // one workgroup per row beyond kMaxWaveM
-constexpr int kMaxWaveM = 8192;  // widest row one wavefront holds in registers
+constexpr int kMaxM = 1 << 24;       // widest row at all (fp32 rows, int32 columns: streamed beyond kMaxBlockM)
+constexpr int kMaxBlockM = 65536;    // widest row one workgroup holds in registers; the limit of the 16-bit and dense forms
+constexpr int kMaxWaveM = 8192;      // widest row one wavefront holds in registers
 constexpr int kBackwardRowsM = 2048;  // backward edge: widest row assembled whole in a wavefront's LDS (8 KiB)
 
 enum Family : int {
   kFamSmall = 0,  // launch_small: even M <= 128 (g = 2) and the scalar-load fallback (g = 1)
   kFamG4 = 1,     // launch_g4_*: fp32, 128-bit loads
   kFamH16 = 2,    // launch_h16_*: half / bfloat16 rows, one wavefront per row
-  kFamBlock = 3   // launch_block_*: one workgroup per row
+  kFamBlock = 3,  // launch_block_*: one workgroup per row, the row in registers
+  kFamStream = 4  // launch_stream: one workgroup per row, the row streamed several times (fp32, int32 columns)
 };
 
 struct Shape {
@@ -78,10 +80,19 @@ inline int block_waves(int M) { return M <= 16384 ? 4 : (M <= 32768 ? 8 : 16); }
 
 // Layout for the pair-output entry points.  `in` is the address of the input matrix (its alignment
 // decides the load width); `plain` = fp32 rows, the k largest, Algorithm 2 or exact mode (the variants
-// that have the 12-groups-per-lane workgroup kernels).  Requires 1 <= M <= kMaxM.
+// that have the 12-groups-per-lane workgroup kernels).  Requires 1 <= M <= kMaxM (kMaxBlockM for 16-bit rows).
 inline Shape classify(int M, int dtype, bool plain, uintptr_t in) {
   Shape s{};
   s.w = 1;
+  if (M > kMaxBlockM) {
+    // streamed: nothing is held, so the "layout" is only the load width (full is never claimed)
+    s.family = kFamStream;
+    s.g = (M % 4 == 0 && is_aligned(in, 16)) ? 4 : 1;
+    s.ng = 0;
+    s.w = 16;
+    s.full = false;
+    return s;
+  }
   if (M > kMaxWaveM) {
     s.family = kFamBlock;
     if (dtype == kF32 && M % 4 == 0 && is_aligned(in, 16)) {
@@ -186,6 +197,8 @@ inline bool instantiated(const Shape& s, int dtype, bool plain, bool dense) {
     case kFamH16:
       if (s.w != 1 || dtype == kF32) return false;
       return (s.g == 8 && in_list(s.ng, 1)) || ((s.g == 4 || s.g == 2) && s.ng == 1) || (s.g == 1 && in_list(s.ng, 2));
+    case kFamStream:
+      return dtype == kF32 && !dense && s.w == 16 && (s.g == 4 || s.g == 1);
     case kFamBlock:
       if (s.g == 1) return s.w == 16 && in_list(s.ng, 3);
       if (s.w != 4 && s.w != 8 && s.w != 16) return false;

@@ -6,8 +6,9 @@
 //   1. the Algorithm 2 hand traces of tests/golden/alg2_handtrace.txt against the sanitized oracle;
 //   2. brute force (a stable sort written out here) against the oracle's exact mode, Algorithm 1 at
 //      epsilon = 0 and the k-smallest variant on tiny tie-heavy rows from the sanitized generator;
-//   3. the shape classification for every row width 1..65536, every element type, both kernel variants
-//      and a set of pointer alignments: the layout returned must be compiled and must hold the row.
+//   3. the shape classification for every row width 1..65536 (and a sample of the streamed widths up to
+//      2^24), every element type, both kernel variants and a set of pointer alignments: the layout
+//      returned must be compiled and must hold the row.
 //
 // Usage: sanitize_main <path to alg2_handtrace.txt>.  Exit code 0 = all checks passed.
 #include <stdint.h>
@@ -154,7 +155,7 @@ static long run_shape_sweep() {
   long n = 0;
   const uintptr_t base = 0x7f0000000000ull;  // never dereferenced: only its alignment is looked at
   const uintptr_t offs[] = {0, 2, 4, 6, 8, 12, 16, 20, 24, 32};
-  for (int M = 1; M <= rtopk::kMaxM; ++M) {
+  for (int M = 1; M <= rtopk::kMaxBlockM; ++M) {
     for (int dtype : {rtopk::kF32, rtopk::kF16, rtopk::kBF16}) {
       const uintptr_t esz = dtype == rtopk::kF32 ? 4 : 2;
       for (uintptr_t off : offs) {
@@ -182,6 +183,19 @@ static long run_shape_sweep() {
               "dense M=%d: load width %d not usable", M, s.g);
         ++n;
       }
+  }
+  // beyond the widest row a workgroup holds: fp32 rows are streamed, with 128-bit loads where they can be
+  for (int64_t M = rtopk::kMaxBlockM + 1; M <= rtopk::kMaxM; M += (M < 70000 ? 1 : 9973)) {
+    for (uintptr_t off : offs) {
+      if (off % 4) continue;
+      for (int plain = 0; plain <= 1; ++plain) {
+        const rtopk::Shape s = rtopk::classify((int)M, rtopk::kF32, plain != 0, base + off);
+        CHECK(s.family == rtopk::kFamStream && rtopk::instantiated(s, rtopk::kF32, plain != 0, false), "M=%ld: not streamed", (long)M);
+        CHECK((s.g == 4) == (M % 4 == 0 && (base + off) % 16 == 0) && (s.g == 4 || s.g == 1), "M=%ld off=%d: load width %d", (long)M,
+              (int)off, s.g);
+        ++n;
+      }
+    }
   }
   // range overlap helper
   CHECK(!rtopk::ranges_overlap(100, 10, 110, 10), "adjacent ranges do not overlap");

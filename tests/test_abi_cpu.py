@@ -38,7 +38,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_limits_and_status_strings(lib):
     assert lib.rtopk_version() >= 100
-    assert lib.rtopk_max_m() == 65536
+    assert lib.rtopk_max_m() == 1 << 24
     seen = set()
     for code in range(0, -9, -1):
         s = lib.rtopk_status_string(code)
@@ -62,11 +62,11 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert f(p, 4, 256, 0, 8, p, p, None) == -2
     assert f(p, 4, 256, 257, 8, p, p, None) == -2
     assert f(p, 4, 256, 32, -1, p, p, None) == -3
-    assert f(p, 4, 65537, 32, 8, p, p, None) == -4
-    assert fe(p, 4, 70000, 32, p, p, None) == -4
+    assert f(p, 4, (1 << 24) + 1, 32, 8, p, p, None) == -4
+    assert fe(p, 4, (1 << 24) + 4, 32, p, p, None) == -4
     assert f(p, 2 ** 31, 9000, 32, 8, p, p, None) == -2   # one workgroup per row beyond 8192 columns: 2^31 - 1 rows
-    assert lib.rtopk_rowwise_smallest(p, 4, 65540, 32, 8, p, p, None) == -4
-    assert lib.rtopk_rowwise_exact_smallest(p, 4, 65540, 32, p, p, None) == -4
+    assert lib.rtopk_rowwise_smallest(p, 4, (1 << 24) + 4, 32, 8, p, p, None) == -4
+    assert lib.rtopk_rowwise_exact_smallest(p, 4, (1 << 24) + 4, 32, p, p, None) == -4
     assert lib.rtopk_rowwise_u8(p, 4, 260, 32, 8, p, p, None) == -4
     assert lib.rtopk_rowwise_exact_u8(p, 4, 260, 32, p, p, None) == -4
     fz = lib.rtopk_rowwise_eps
@@ -76,7 +76,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fz(p, 4, 256, 32, float("nan"), p, p, None, None) == -7
     assert fz(p, 0, 256, 32, 0.5, None, None, None, None) == 0
     assert fz(p, 4, 256, 32, 0.5, p, p, p + 2, None) == -5
-    assert fz(p, 4, 65540, 32, 0.5, p, p, None, None) == -4
+    assert fz(p, 4, (1 << 24) + 4, 32, 0.5, p, p, None, None) == -4
     assert f(p + 2, 4, 256, 32, 8, p, p, None) == -5
     assert f(p, 4, 256, 32, 8, p + 1, p, None) == -5
     assert f(p, 4, 256, 32, 8, p, p + 2, None) == -5
@@ -193,7 +193,7 @@ def test_header_is_plain_c_and_links_from_c(tmp_path, lib):
     src.write_text(
         '#include "rtopk.h"\n#include <stdio.h>\n'
         "int main(void) {\n"
-        "  if (rtopk_max_m() != 65536 || rtopk_version() < 100) return 1;\n"
+        "  if (rtopk_max_m() != (1 << 24) || rtopk_version() < 100) return 1;\n"
         "  /* argument errors are reported on the host, before any launch */\n"
         "  if (rtopk_rowwise(0, 4, 256, 32, 8, 0, 0, 0) != RTOPK_ERR_NULL_POINTER) return 2;\n"
         "  if (rtopk_rowwise_exact((const float*)64, 4, 256, 300, (float*)64, (int32_t*)64, 0) != RTOPK_ERR_BAD_SHAPE) return 3;\n"
@@ -248,6 +248,7 @@ def test_every_expected_kernel_family_is_in_the_built_library():
                    "rtopk::rtopk_dense_kernel<4, 1, 4, true, 1>",
                    "rtopk::rtopk_wave_kernel<4, 1, 8, true, 1, false, unsigned char, 0>",  # byte-wide columns keep 8 rows
                    "rtopk::rtopk_block_kernel<4, 16, 8, 1, false, 0, false>",        # M = 32768
+                   "rtopk::rtopk_stream_kernel<4, 1, false>",                        # M > 65536
                    "rtopk::maxk_scatter_rows_kernel<int, 8, true>",
                    "rtopk::maxk_gather_rows_kernel<unsigned char, 8, true>"):
         assert needle in syms, needle

@@ -141,6 +141,8 @@ CONFIGS = {
     # beyond the paper's widest row (Appendix B stops at M = 8192): one workgroup per row
     "x_wide32k": dict(N=8192, M=32768, seed=5, dist="laplace", ks=(256, 2048), max_iters=(), idx="int32"),
     "x_wide64k": dict(N=4096, M=65536, seed=6, dist="laplace", ks=(512,), max_iters=(), idx="int32"),
+    # rows that no longer fit a workgroup's registers: streamed, eight search steps per pass
+    "x_stream256k": dict(N=1024, M=262144, seed=7, dist="laplace", ks=(512,), max_iters=(), idx="int32"),
 }
 
 
