@@ -35,22 +35,28 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
   return v;
 }
 
-// Number of this lane's E keys that are below t, from the sign bits of key - t (see count_ge_wide: two
-// full-rate vector instructions per element, no scalar work).
+// The sign bits of key - t for this lane's E keys, 32 to a word: element e is bit (filled - 1 - e % 32) of
+// word e / 32 (filled = elements in that word; the bits above them stay zero), set when key < t.  Two
+// full-rate vector instructions per element and no scalar work (see count_ge_wide).
 template <int E, bool NEG>
-__device__ __forceinline__ uint32_t lane_count_below(const float (&x)[E], float t) {
+__device__ __forceinline__ void lane_below_packs(const float (&x)[E], float t, uint32_t (&p)[(E + 31) / 32]) {
   const float tz = (t == 0.0f) ? -0.0f : t;
-  uint32_t below = 0, pack = 0;
+  uint32_t pack = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const float d = keyof<NEG>(x[e]) - tz;
     pack = __builtin_amdgcn_alignbit(pack, __float_as_uint(d), 31);  // (pack << 1) | sign(d)
     if ((e & 31) == 31 || e + 1 == E) {
-      below += (uint32_t)__builtin_popcount(pack);
+      p[e / 32] = pack;
       pack = 0;
     }
   }
-  return below;
+}
+
+// All ones in the bits of word `word` that lane_below_packs fills.
+template <int E>
+constexpr uint32_t pack_valid(int word) {
+  return (word == (E + 31) / 32 - 1 && E % 32 != 0) ? ((1u << (E % 32)) - 1u) : 0xffffffffu;
 }
 
 // Sum over each row of 16 lanes; every lane of a row ends up with its row's total.
@@ -74,38 +80,35 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan_dpp(uint32_t v) {
 }
 
 typedef __attribute__((address_space(3))) float lds_float;
+
+// (a & mask) | (b & ~mask) in one instruction.
+__device__ __forceinline__ uint32_t select_bits(uint32_t mask, uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(mask), "v"(a), "v"(b));
+  return r;
+}
+
 constexpr uint32_t kNoRoom = 0xffffffffu;
 
 // The wavefront's members of the band lo <= key < hi go to consecutive 4-byte slots of LDS, in any order.
-// Every lane first finds its own members from the sign bits of key - lo and key - hi (four full-rate
-// vector instructions per element, no scalar work); the lanes' counts are scanned, `reserve(n, above)`
-// returns the byte address of n free slots, or kNoRoom (and is told how many keys are at or above hi); then each
-// lane walks its elements once more and stores every one of them -- members to the lane's next slot,
-// the others to a per-lane dummy word at `dummy` -- so that no lane mask or branch is needed.
+// below_lo and below_hi are the lane's sign-bit words against the two bounds (lane_below_packs); the
+// search has them already, from the steps that set the bounds.  The lanes' member counts are scanned,
+// `reserve(n, above)` returns the byte address of n free slots, or kNoRoom (and is told how many keys are
+// at or above hi); then each lane walks its elements once and stores every one of them -- members to the
+// lane's next slot, the others to a per-lane dummy word at `dummy` -- so that no lane mask or branch is
+// needed.
 template <int E, bool NEG, typename Reserve>
-__device__ __forceinline__ void scatter_band_members(const float (&x)[E], float lo, float hi, int lane, uint32_t dummy,
-                                                     Reserve reserve) {
+__device__ __forceinline__ void scatter_band_members(const float (&x)[E], const uint32_t (&below_lo)[(E + 31) / 32],
+                                                     const uint32_t (&below_hi)[(E + 31) / 32], int lane,
+                                                     uint32_t dummy, Reserve reserve) {
   constexpr int GROUPS = (E + 31) / 32;
-  const float loz = (lo == 0.0f) ? -0.0f : lo, hiz = (hi == 0.0f) ? -0.0f : hi;
   uint32_t member[GROUPS];
   uint32_t n_lane = 0, above_lane = 0;
-  {
-    uint32_t pl = 0, ph = 0;
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-      const float key = keyof<NEG>(x[e]);
-      pl = __builtin_amdgcn_alignbit(pl, __float_as_uint(key - loz), 31);  // sign set: key < lo
-      ph = __builtin_amdgcn_alignbit(ph, __float_as_uint(key - hiz), 31);  // sign set: key < hi
-      if ((e & 31) == 31 || e + 1 == E) {
-        const int filled = (e & 31) + 1;  // element j of the group sits at bit filled - 1 - j
-        const uint32_t valid = filled == 32 ? 0xffffffffu : ((1u << filled) - 1u);
-        member[e / 32] = ~pl & ph & valid;
-        n_lane += (uint32_t)__builtin_popcount(member[e / 32]);
-        above_lane += (uint32_t)__builtin_popcount(~ph & valid);
-        pl = 0;
-        ph = 0;
-      }
-    }
+  for (int g = 0; g < GROUPS; ++g) {
+    member[g] = ~below_lo[g] & below_hi[g];
+    n_lane += (uint32_t)__builtin_popcount(member[g]);
+    above_lane += (uint32_t)__builtin_popcount(~below_hi[g] & pack_valid<E>(g));
   }
   const uint32_t incl = wave_inclusive_scan_dpp(n_lane);
   const uint32_t n_wave = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
@@ -124,10 +127,11 @@ __device__ __forceinline__ void scatter_band_members(const float (&x)[E], float 
   for (int e = 0; e < E; ++e) {
     const int filled = (e / 32 == GROUPS - 1 && E % 32 != 0) ? E % 32 : 32;
     const int bit = filled - 1 - (e & 31);
-    const int m = ((int)(member[e / 32] << (31 - bit))) >> 31;  // -1 for a member, 0 otherwise
-    const uint32_t a = (addr & (uint32_t)m) | (trash & ~(uint32_t)m);
-    *reinterpret_cast<lds_float*>(a) = x[e];
-    addr += (uint32_t)(m * 4);  // one slot down after a member
+    // three vector instructions per element, written out because the compiler otherwise rebuilds the
+    // select from a compare and a conditional move and the address from a running count (seven)
+    const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe(member[e / 32], (uint32_t)bit, 1u);  // all ones for a member
+    *reinterpret_cast<lds_float*>(select_bits(m, addr, trash)) = x[e];
+    asm("v_lshl_add_u32 %0, %1, 2, %0" : "+v"(addr) : "v"(m));  // one slot down after a member
   }
 }
 
@@ -156,6 +160,80 @@ __device__ __forceinline__ void store_pair_masked(uint64_t mask, void* vals, uin
         : "=&s"(saved)
         : "s"(mask), "v"(off_v), "v"(value_bits), "s"(vals), "v"(off_c), "v"(col), "s"(cols)
         : "memory", "scc");
+  }
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order.
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// The lane's candidate bits against t: lane_below_packs' layout, set when key >= t.  The same sign-bit
+// test as the search's counts, so the set bits of a lane number exactly the keys not counted as below t.
+template <int E, bool NEG>
+__device__ __forceinline__ void lane_bits_at_or_above(const float (&x)[E], float t, uint32_t (&w)[(E + 31) / 32]) {
+  lane_below_packs<E, NEG>(x, t, w);
+#pragma unroll
+  for (int g = 0; g < (E + 31) / 32; ++g) w[g] = ~w[g] & pack_valid<E>(g);
+}
+
+// The G bits of elements g*G .. g*G + G - 1 out of lane_bits_at_or_above's words; element g*G is the
+// highest of them.  G divides 32, so a group never straddles two words.
+template <int E, int G>
+__device__ __forceinline__ uint32_t group_bits(const uint32_t (&w)[(E + 31) / 32], int g) {
+  static_assert(32 % G == 0, "a group must not straddle two words");
+  const int e0 = g * G, word = e0 / 32;
+  const int filled = (word == (E + 31) / 32 - 1 && E % 32 != 0) ? E % 32 : 32;
+  return __builtin_amdgcn_ubfe(w[word], (uint32_t)(filled - (e0 % 32) - G), (uint32_t)G);
+}
+
+// In the lanes where pos < limit (unsigned; a lane that must not store passes pos = 0xffffffff): the value
+// goes to slot pos of vals and col0 + C to slot pos of cols.  The compare leaves its mask in VCC; when
+// no lane stores -- the usual case when k is a small part of the row -- one branch skips everything,
+// and otherwise the mask becomes the set of active lanes for the address arithmetic and the two
+// stores, with no work on the scalar unit beyond saving and restoring that set.
+template <int DT, int C>
+__device__ __forceinline__ void store_pair_if_below(uint32_t pos, uint32_t limit, void* vals, uint32_t value_bits,
+                                                    int32_t* cols, int32_t col0) {
+  uint64_t saved;
+  uint32_t t1, t2;
+  if constexpr (DT == kF32) {
+    asm volatile(
+        "v_cmp_gt_u32 vcc, %[lim], %[pos]\n\t"
+        "s_cbranch_vccz 1f\n\t"
+        "s_and_saveexec_b64 %[sv], vcc\n\t"
+        "v_lshlrev_b32 %[t1], 2, %[pos]\n\t"
+        "v_add_u32 %[t2], %[c], %[col0]\n\t"
+        "global_store_dword %[t1], %[val], %[vals]\n\t"
+        "global_store_dword %[t1], %[t2], %[cols]\n\t"
+        "s_mov_b64 exec, %[sv]\n"
+        "1:"
+        : [sv] "=&s"(saved), [t1] "=&v"(t1), [t2] "=&v"(t2)
+        : [lim] "s"(limit), [pos] "v"(pos), [c] "n"(C), [col0] "v"(col0), [val] "v"(value_bits), [vals] "s"(vals),
+          [cols] "s"(cols)
+        : "memory", "scc", "vcc");
+  } else {
+    uint32_t t3;
+    asm volatile(
+        "v_cmp_gt_u32 vcc, %[lim], %[pos]\n\t"
+        "s_cbranch_vccz 1f\n\t"
+        "s_and_saveexec_b64 %[sv], vcc\n\t"
+        "v_lshlrev_b32 %[t1], 2, %[pos]\n\t"
+        "v_lshlrev_b32 %[t3], 1, %[pos]\n\t"
+        "v_add_u32 %[t2], %[c], %[col0]\n\t"
+        "global_store_short %[t3], %[val], %[vals]\n\t"
+        "global_store_dword %[t1], %[t2], %[cols]\n\t"
+        "s_mov_b64 exec, %[sv]\n"
+        "1:"
+        : [sv] "=&s"(saved), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3)
+        : [lim] "s"(limit), [pos] "v"(pos), [c] "n"(C), [col0] "v"(col0), [val] "v"(value_bits), [vals] "s"(vals),
+          [cols] "s"(cols)
+        : "memory", "scc", "vcc");
   }
 }
 
@@ -244,8 +322,14 @@ __global__ void __launch_bounds__(W * kWave)
   // (Adding the lanes' counts to one LDS word with atomics instead, which saves the second reduction,
   // measured slower: 8192 x 32768 at eight steps 252 -> 266 us.)
   int step = 0;
+  constexpr int kPackWords = (E + 31) / 32;
+  uint32_t last[kPackWords];  // this lane's sign-bit words of the latest count
   auto count = [&](float t) -> int {
-    const int mine = wave_sum((int)lane_count_below<E, NEG>(x, t));
+    lane_below_packs<E, NEG>(x, t, last);
+    uint32_t below_lane = 0;
+#pragma unroll
+    for (int g = 0; g < kPackWords; ++g) below_lane += (uint32_t)__builtin_popcount(last[g]);
+    const int mine = wave_sum((int)below_lane);
     const int p = step & 1;
     ++step;
     if (lane == 0) s_cnt[p][wave] = mine;
@@ -270,7 +354,19 @@ __global__ void __launch_bounds__(W * kWave)
     const float eps = MODE == kEps ? eps_rel * __builtin_fabsf(hi) : 0.0f;
     // (Narrowing as soon as the band fits stays the fastest: never narrowing costs 3 % on Laplace rows --
     // 12.3 full-width steps on average at 32768 columns -- and starting only after 8 to 14 steps 7-12 %.)
+    // the sign-bit words of the steps that set the current lo and hi: the gather needs no compare of its own
+    uint32_t below_lo[kPackWords], below_hi[kPackWords];
+    bool lo_moved = false, hi_moved = false;
     auto fits = [&](int cnt) -> bool {  // after move_bound with this count
+      if (cnt < k) {  // uniform
+        hi_moved = true;
+#pragma unroll
+        for (int g = 0; g < kPackWords; ++g) below_hi[g] = last[g];
+      } else {
+        lo_moved = true;
+#pragma unroll
+        for (int g = 0; g < kPackWords; ++g) below_lo[g] = last[g];
+      }
       cnt_lo = cnt < k ? cnt_lo : cnt;
       cnt_hi = cnt < k ? cnt : cnt_hi;
       return cnt_lo - cnt_hi <= kBandRegs * kWave;
@@ -324,7 +420,9 @@ __global__ void __launch_bounds__(W * kWave)
     if (narrow) {  // uniform over the workgroup
       // every wavefront appends its band members to the row's band (any order will do)
       const uint32_t dst = (uint32_t)(uintptr_t)s_band;
-      scatter_band_members<E, NEG>(x, lo, hi, lane, dst + (uint32_t)((kBandRegs + wave) * kWave) * 4u,
+      if (!lo_moved) lane_below_packs<E, NEG>(x, lo, below_lo);  // a bound still at the row's minimum or maximum
+      if (!hi_moved) lane_below_packs<E, NEG>(x, hi, below_hi);
+      scatter_band_members<E, NEG>(x, below_lo, below_hi, lane, dst + (uint32_t)((kBandRegs + wave) * kWave) * 4u,
                                    [&](uint32_t n, uint32_t above) -> uint32_t {
                                      uint32_t off = 0;
                                      if (lane == 0) {
@@ -384,20 +482,55 @@ __global__ void __launch_bounds__(W * kWave)
   const bool has_b = limB > 0;  // uniform over the workgroup
 
   // Ranking, part 1: candidates per (group, wavefront) cell, written in column order.
+  //
+  // One class (every search that ended on a count of k, and Algorithm 2): all per lane.  Each lane takes
+  // its elements' candidate bits from the sign of key - tA, counts them per group, and the counts of up to
+  // three groups share one word (10 bits each: a wavefront holds at most 64 * 8 candidates of a group)
+  // through one prefix scan over the lanes.  The scan's last lane holds the cell totals, every lane keeps
+  // the candidates in lower lanes for part 3.  Against one mask, one scalar popcount and one scalar add per
+  // ELEMENT this leaves the scalar unit, which the 16 wavefronts of two rows share, nearly idle.
+  constexpr bool kLaneRank = G > 1;      // the scalar-load fallback (G = 1) keeps the mask form
+  constexpr int kScanWords = (NG + 2) / 3;
+  uint32_t cand[(E + 31) / 32];          // candidate bits of this lane
+  uint32_t lower[kScanWords];            // per group, 10 bits each: candidates of the cell in lower lanes
+  uint32_t cell_total[kScanWords];       // the same fields for the whole wavefront (uniform)
+  if (kLaneRank && !has_b) {
+    lane_bits_at_or_above<E, NEG>(x, tA, cand);
+    uint32_t own[kScanWords];
 #pragma unroll
-  for (int g = 0; g < NG; ++g) {
-    int nA = 0, nB = 0;
+    for (int j = 0; j < kScanWords; ++j) own[j] = 0;
 #pragma unroll
-    for (int c = 0; c < G; ++c) {
-      const float v = keyof<NEG>(x[g * G + c]);
-      nA += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v >= tA));
-      if (has_b) nB += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v >= tB && !(v >= tA)));
+    for (int g = 0; g < NG; ++g)
+      own[g / 3] |= (uint32_t)__builtin_popcount(group_bits<E, G>(cand, g)) << (10 * (g % 3));
+#pragma unroll
+    for (int j = 0; j < kScanWords; ++j) {
+      const uint32_t incl = wave_inclusive_scan_dpp(own[j]);
+      lower[j] = incl - own[j];  // field by field: no field borrows, incl >= own in each
+      cell_total[j] = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
     }
-    if (lane == 0) {
-      s_tab[0][g * W + wave] = nA;
-      s_tab[1][g * W + wave] = nB;
+    if (lane < NG) {
+      // lane g posts cell g (the totals are uniform; the shift is per lane)
+      uint32_t word = cell_total[0];
+#pragma unroll
+      for (int j = 1; j < kScanWords; ++j) word = lane / 3 == j ? cell_total[j] : word;
+      s_tab[0][lane * W + wave] = (int)((word >> (10 * (lane % 3))) & 0x3ffu);
     }
-    if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);  // keep the groups' masks from piling up
+  } else {
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      int nA = 0, nB = 0;
+#pragma unroll
+      for (int c = 0; c < G; ++c) {
+        const float v = keyof<NEG>(x[g * G + c]);
+        nA += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v >= tA));
+        if (has_b) nB += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v >= tB && !(v >= tA)));
+      }
+      if (lane == 0) {
+        s_tab[0][g * W + wave] = nA;
+        s_tab[1][g * W + wave] = nB;
+      }
+      if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);  // keep the groups' masks from piling up
+    }
   }
   __syncthreads();
   // Part 2: exclusive prefix over the cells (wavefront 0 scans class A, wavefront 1 class B).
@@ -427,6 +560,47 @@ __global__ void __launch_bounds__(W * kWave)
   using OutT = typename std::conditional<DT == kF32, uint32_t, uint16_t>::type;  // value bits as stored
   OutT* ov = static_cast<OutT*>(out_vals) + r * (int64_t)(DENSE ? M : k);
   int32_t* oi = DENSE ? nullptr : out_idx + r * (int64_t)k;
+  if (kLaneRank && !has_b) {
+    // One class, per lane: rank = cell prefix + candidates of the cell in lower lanes + own earlier
+    // candidates in the group.  A lane's non-candidates get rank 0xffffffff, so that the one compare against
+    // limA (which also keeps every store inside the row's k slots whatever the input held) decides who
+    // stores.  Cells without a candidate are skipped as a whole.
+    // lane g fetches the prefix of cell g: one LDS round trip for all the wavefront's cells
+    const int my_cell = s_tab[0][(lane < NG ? lane : 0) * W + wave];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      if constexpr (!DENSE) {
+        if (((cell_total[g / 3] >> (10 * (g % 3))) & 0x3ffu) == 0) continue;  // uniform
+      }
+      int ln = lane;  // opaque per group: keeps the column numbers of all groups from being hoisted
+      if constexpr (NG > 4) asm volatile("" : "+v"(ln));
+      const uint32_t bits = group_bits<E, G>(cand, g);
+      const uint32_t before = (uint32_t)__builtin_amdgcn_readlane(my_cell, g) +
+                              __builtin_amdgcn_ubfe(lower[g / 3], (uint32_t)(10 * (g % 3)), 10u);
+      const int col0 = ((g * W + wave) * kWave + ln) * G;
+      float y[G];
+      auto one = [&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        const uint32_t pos = before + (c == 0 ? 0u : (uint32_t)__builtin_popcount(bits >> (G - c)));
+        const uint32_t is_cand = (uint32_t)__builtin_amdgcn_sbfe(bits, (uint32_t)(G - 1 - c), 1u);  // all ones or zero
+        const uint32_t rank = pos | ~is_cand;
+        if constexpr (DENSE) {
+          y[c] = rank < (uint32_t)limA ? x[g * G + c] : 0.0f;
+        } else {
+          const uint32_t fb = __float_as_uint(x[g * G + c]);
+          uint32_t vb = fb;
+          if constexpr (DT != kF32) vb = narrow_bits<DT>(fb);
+          store_pair_if_below<DT, c>(rank, (uint32_t)limA, ov, vb, oi, col0);
+        }
+      };
+      static_for<G>(one);
+      if constexpr (DENSE) {
+        if (col0 < M) store_group<G>(reinterpret_cast<float*>(ov) + col0, y);
+      }
+      if constexpr (NG > 4) __builtin_amdgcn_sched_barrier(0);
+    }
+    return;
+  }
   if (!has_b) {
     // One class: rank = cell prefix + chosen elements in lower lanes + own earlier elements.
 #pragma unroll

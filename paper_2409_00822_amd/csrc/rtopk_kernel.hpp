@@ -22,6 +22,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "rtopk_dispatch.hpp"
 
