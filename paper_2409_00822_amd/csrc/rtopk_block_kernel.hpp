@@ -35,30 +35,6 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
   return v;
 }
 
-// The sign bits of key - t for this lane's E keys, 32 to a word: element e is bit (filled - 1 - e % 32) of
-// word e / 32 (filled = elements in that word; the bits above them stay zero), set when key < t.  Two
-// full-rate vector instructions per element and no scalar work (see count_ge_wide).
-template <int E, bool NEG>
-__device__ __forceinline__ void lane_below_packs(const float (&x)[E], float t, uint32_t (&p)[(E + 31) / 32]) {
-  const float tz = (t == 0.0f) ? -0.0f : t;
-  uint32_t pack = 0;
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const float d = keyof<NEG>(x[e]) - tz;
-    pack = __builtin_amdgcn_alignbit(pack, __float_as_uint(d), 31);  // (pack << 1) | sign(d)
-    if ((e & 31) == 31 || e + 1 == E) {
-      p[e / 32] = pack;
-      pack = 0;
-    }
-  }
-}
-
-// All ones in the bits of word `word` that lane_below_packs fills.
-template <int E>
-constexpr uint32_t pack_valid(int word) {
-  return (word == (E + 31) / 32 - 1 && E % 32 != 0) ? ((1u << (E % 32)) - 1u) : 0xffffffffu;
-}
-
 // Sum over each row of 16 lanes; every lane of a row ends up with its row's total.
 __device__ __forceinline__ uint32_t row16_sum(uint32_t v) {
   v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
@@ -66,73 +42,6 @@ __device__ __forceinline__ uint32_t row16_sum(uint32_t v) {
   v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);  // row_half_mirror
   v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, false);  // row_mirror
   return v;
-}
-
-// Inclusive prefix sum over the 64 lanes with six DPP steps (a lane without a source keeps 0 added).
-__device__ __forceinline__ uint32_t wave_inclusive_scan_dpp(uint32_t v) {
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);  // row_shr:1
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);  // row_shr:2
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);  // row_shr:4
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);  // row_shr:8
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
-  return v;
-}
-
-typedef __attribute__((address_space(3))) float lds_float;
-
-// (a & mask) | (b & ~mask) in one instruction.
-__device__ __forceinline__ uint32_t select_bits(uint32_t mask, uint32_t a, uint32_t b) {
-  uint32_t r;
-  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(mask), "v"(a), "v"(b));
-  return r;
-}
-
-constexpr uint32_t kNoRoom = 0xffffffffu;
-
-// The wavefront's members of the band lo <= key < hi go to consecutive 4-byte slots of LDS, in any order.
-// below_lo and below_hi are the lane's sign-bit words against the two bounds (lane_below_packs); the
-// search has them already, from the steps that set the bounds.  The lanes' member counts are scanned,
-// `reserve(n, above)` returns the byte address of n free slots, or kNoRoom (and is told how many keys are
-// at or above hi); then each lane walks its elements once and stores every one of them -- members to the
-// lane's next slot, the others to a per-lane dummy word at `dummy` -- so that no lane mask or branch is
-// needed.
-template <int E, bool NEG, typename Reserve>
-__device__ __forceinline__ void scatter_band_members(const float (&x)[E], const uint32_t (&below_lo)[(E + 31) / 32],
-                                                     const uint32_t (&below_hi)[(E + 31) / 32], int lane,
-                                                     uint32_t dummy, Reserve reserve) {
-  constexpr int GROUPS = (E + 31) / 32;
-  uint32_t member[GROUPS];
-  uint32_t n_lane = 0, above_lane = 0;
-#pragma unroll
-  for (int g = 0; g < GROUPS; ++g) {
-    member[g] = ~below_lo[g] & below_hi[g];
-    n_lane += (uint32_t)__builtin_popcount(member[g]);
-    above_lane += (uint32_t)__builtin_popcount(~below_hi[g] & pack_valid<E>(g));
-  }
-  const uint32_t incl = wave_inclusive_scan_dpp(n_lane);
-  const uint32_t n_wave = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-  const uint32_t above = (uint32_t)wave_sum((int)above_lane);
-  const uint32_t base = reserve(n_wave, above);  // wave-uniform LDS byte address, or kNoRoom
-  if (base == kNoRoom) {
-    // cannot happen on finite input (the caller has bounded the band by its counts); with NaN or
-    // infinite keys the sign bits need not agree with those counts, and then nothing is stored
-#pragma unroll
-    for (int g = 0; g < GROUPS; ++g) member[g] = 0;
-  }
-  // the lane's slots are filled from its last one downwards
-  uint32_t addr = base + (incl - 1u) * 4u;
-  const uint32_t trash = dummy + (uint32_t)lane * 4u;
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int filled = (e / 32 == GROUPS - 1 && E % 32 != 0) ? E % 32 : 32;
-    const int bit = filled - 1 - (e & 31);
-    // three vector instructions per element, written out because the compiler otherwise rebuilds the
-    // select from a compare and a conditional move and the address from a running count (seven)
-    const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe(member[e / 32], (uint32_t)bit, 1u);  // all ones for a member
-    *reinterpret_cast<lds_float*>(select_bits(m, addr, trash)) = x[e];
-    asm("v_lshl_add_u32 %0, %1, 2, %0" : "+v"(addr) : "v"(m));  // one slot down after a member
-  }
 }
 
 // In the lanes whose bit is set in `mask` (a subset of the active lanes): the 32-bit (or, for 16-bit
@@ -241,10 +150,11 @@ __device__ __forceinline__ void store_pair_if_below(uint32_t pos, uint32_t limit
 // at 8 wavefronts per workgroup, two rows per compute unit.  Forcing 80 registers (a third row per
 // compute unit, at the price of 5 spilled registers) measured no faster in exact mode and 7-15 % slower
 // with early stopping, so the allocation is left to the compiler.
+// One row, by the whole workgroup.  Every wavefront leaves through the same return statement.
 template <int G, int NG, int W, int MODE, bool NEG, int DT, bool DENSE>
-__global__ void __launch_bounds__(W * kWave)
-    rtopk_block_kernel(const void* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
-                       void* __restrict__ out_vals, int32_t* __restrict__ out_idx, int32_t* __restrict__ out_iters) {
+__device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in, int64_t N, int M, int k, int max_iter,
+                                          float eps_rel, void* __restrict__ out_vals, int32_t* __restrict__ out_idx,
+                                          int32_t* __restrict__ out_iters) {
   static_assert(!DENSE || DT == kF32, "the dense form is built for fp32 rows");
   constexpr int E = G * NG;
   constexpr int T = NG * W;  // (group, wavefront) cells of a row, in column order
@@ -262,8 +172,6 @@ __global__ void __launch_bounds__(W * kWave)
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int64_t r = blockIdx.x;
-  if (r >= N) return;
   const ElemT* row = static_cast<const ElemT*>(in) + r * (int64_t)M;
 
   // Loading stage.  Lanes past M load the row's first columns (in bounds, cannot change min or max).
@@ -680,10 +588,44 @@ __global__ void __launch_bounds__(W * kWave)
   }
 }
 
+// Workgroup b takes rows b, b + gridDim.x, ...: with as many workgroups as rows each takes one; the widest
+// shape (16 wavefronts, one workgroup to a compute unit) is launched with one workgroup per compute unit
+// instead, which saves the dispatch of a new 1024-thread workgroup between a unit's rows.
+template <int G, int NG, int W, int MODE, bool NEG, int DT, bool DENSE>
+__global__ void __launch_bounds__(W * kWave)
+    rtopk_block_kernel(const void* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
+                       void* __restrict__ out_vals, int32_t* __restrict__ out_idx, int32_t* __restrict__ out_iters) {
+  for (int64_t r = blockIdx.x; r < N; r += gridDim.x) {
+    block_row<G, NG, W, MODE, NEG, DT, DENSE>(r, in, N, M, k, max_iter, eps_rel, out_vals, out_idx, out_iters);
+    __syncthreads();  // the next row reuses the shared tables
+  }
+}
+
+// Compute units of the current device (asked once per device; concurrent first calls store the same value).
+inline int compute_units() {
+  static int units[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (units[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    units[dev] = n;
+  }
+  return units[dev];
+}
+
+#ifndef RTOPK_BLOCK_PERSIST
+#define RTOPK_BLOCK_PERSIST 1
+#endif
 template <int G, int NG, int W, int MODE, bool NEG = false, int DT = kF32, bool DENSE = false>
 hipError_t launch_block(const LaunchArgs& a) {
   if (a.N > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  return launch_kernel(rtopk_block_kernel<G, NG, W, MODE, NEG, DT, DENSE>, dim3((unsigned)a.N), dim3(W * kWave), 0,
+  int64_t grid = a.N;
+  if (RTOPK_BLOCK_PERSIST && W == 16) {
+    const int units = compute_units();
+    if (units > 0 && grid > units) grid = units;
+  }
+  return launch_kernel(rtopk_block_kernel<G, NG, W, MODE, NEG, DT, DENSE>, dim3((unsigned)grid), dim3(W * kWave), 0,
                        a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
                        static_cast<int32_t*>(a.out_idx), a.out_iters);
 }

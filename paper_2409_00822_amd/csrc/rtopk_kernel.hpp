@@ -520,6 +520,97 @@ constexpr int band_regs(int E) { return E >= 128 ? 8 : kBandRegs; }
 // row to a wavefront, so that the row's staging area is still unused while it is searched.
 constexpr bool narrows(int E, int /*mode*/) { return E >= 24; }
 
+// The sign bits of key - t for this lane's E keys, 32 to a word: element e is bit (filled - 1 - e % 32) of
+// word e / 32 (filled = elements in that word; the bits above them stay zero), set when key < t.  Two
+// full-rate vector instructions per element and no scalar work (see count_ge_wide).
+template <int E, bool NEG>
+__device__ __forceinline__ void lane_below_packs(const float (&x)[E], float t, uint32_t (&p)[(E + 31) / 32]) {
+  const float tz = (t == 0.0f) ? -0.0f : t;
+  uint32_t pack = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const float d = keyof<NEG>(x[e]) - tz;
+    pack = __builtin_amdgcn_alignbit(pack, __float_as_uint(d), 31);  // (pack << 1) | sign(d)
+    if ((e & 31) == 31 || e + 1 == E) {
+      p[e / 32] = pack;
+      pack = 0;
+    }
+  }
+}
+
+// All ones in the bits of word `word` that lane_below_packs fills.
+template <int E>
+constexpr uint32_t pack_valid(int word) {
+  return (word == (E + 31) / 32 - 1 && E % 32 != 0) ? ((1u << (E % 32)) - 1u) : 0xffffffffu;
+}
+
+// Inclusive prefix sum over the 64 lanes with six DPP steps (a lane without a source keeps 0 added).
+__device__ __forceinline__ uint32_t wave_inclusive_scan_dpp(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+typedef __attribute__((address_space(3))) float lds_float;
+
+// (a & mask) | (b & ~mask) in one instruction.
+__device__ __forceinline__ uint32_t select_bits(uint32_t mask, uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(mask), "v"(a), "v"(b));
+  return r;
+}
+
+constexpr uint32_t kNoRoom = 0xffffffffu;
+
+// The wavefront's members of the band lo <= key < hi go to consecutive 4-byte slots of LDS, in any order.
+// below_lo and below_hi are the lane's sign-bit words against the two bounds (lane_below_packs); the
+// search has them already, from the steps that set the bounds.  The lanes' member counts are scanned,
+// `reserve(n, above)` returns the byte address of n free slots, or kNoRoom (and is told how many keys are
+// at or above hi); then each lane walks its elements once and stores every one of them -- members to the
+// lane's next slot, the others to a per-lane dummy word at `dummy` -- so that no lane mask or branch is
+// needed.
+template <int E, bool NEG, typename Reserve>
+__device__ __forceinline__ void scatter_band_members(const float (&x)[E], const uint32_t (&below_lo)[(E + 31) / 32],
+                                                     const uint32_t (&below_hi)[(E + 31) / 32], int lane,
+                                                     uint32_t dummy, Reserve reserve) {
+  constexpr int GROUPS = (E + 31) / 32;
+  uint32_t member[GROUPS];
+  uint32_t n_lane = 0, above_lane = 0;
+#pragma unroll
+  for (int g = 0; g < GROUPS; ++g) {
+    member[g] = ~below_lo[g] & below_hi[g];
+    n_lane += (uint32_t)__builtin_popcount(member[g]);
+    above_lane += (uint32_t)__builtin_popcount(~below_hi[g] & pack_valid<E>(g));
+  }
+  const uint32_t incl = wave_inclusive_scan_dpp(n_lane);
+  const uint32_t n_wave = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+  const uint32_t above = (uint32_t)wave_sum((int)above_lane);
+  const uint32_t base = reserve(n_wave, above);  // wave-uniform LDS byte address, or kNoRoom
+  if (base == kNoRoom) {
+    // cannot happen on finite input (the caller has bounded the band by its counts); with NaN or
+    // infinite keys the sign bits need not agree with those counts, and then nothing is stored
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) member[g] = 0;
+  }
+  // the lane's slots are filled from its last one downwards
+  uint32_t addr = base + (incl - 1u) * 4u;
+  const uint32_t trash = dummy + (uint32_t)lane * 4u;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int filled = (e / 32 == GROUPS - 1 && E % 32 != 0) ? E % 32 : 32;
+    const int bit = filled - 1 - (e & 31);
+    // three vector instructions per element, written out because the compiler otherwise rebuilds the
+    // select from a compare and a conditional move and the address from a running count (seven)
+    const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe(member[e / 32], (uint32_t)bit, 1u);  // all ones for a member
+    *reinterpret_cast<lds_float*>(select_bits(m, addr, trash)) = x[e];
+    asm("v_lshl_add_u32 %0, %1, 2, %0" : "+v"(addr) : "v"(m));  // one slot down after a member
+  }
+}
+
 // y[j] = the (lane + 64 j)-th of the nb floats at LDS address `scratch`, or a key of -inf beyond them.
 // The LDS queue of a wavefront is served in order, so the reads see the wavefront's earlier writes; the
 // wait is written out because the compiler does not track LDS operations inside asm blocks.
@@ -619,6 +710,13 @@ __device__ __forceinline__ void search_band(const float (&band)[BR], int above, 
 #ifndef RTOPK_ACC_OF
 #define RTOPK_ACC_OF(E) ((E) >= 96 ? (E) : ((E) >= 64 ? (2 * (E)) / 3 : ((E) - 3) / 3))
 #endif
+// Rows whose every element is counted per lane gather their band from the sign-bit words of the search
+// (see select_row); the scatter needs one dummy word per lane behind the band's slots.
+constexpr bool scatter_gathers(int E) { return E > 8 && narrows(E, 0) && RTOPK_ACC_OF(E) == (E); }
+// Floats of LDS scratch per wavefront that the narrowing of a row of E values per lane uses (0: none).
+constexpr int band_scratch_floats(int E) {
+  return narrows(E, 0) ? band_regs(E) * kWave + (scatter_gathers(E) ? kWave : 0) : 0;
+}
 
 // Search and selection for one row held as xin[E] (lanes past column M hold duplicates of real
 // elements on entry).
@@ -654,11 +752,55 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
   constexpr int ACC = KEEP ? 0 : RTOPK_ACC_OF(E);
   constexpr int BR = band_regs(E);  // registers per lane of a gathered band (see gather_band)
   uint64_t m[KEEP ? E : 1];
+  // Rows counted entirely per lane keep the sign-bit words of the steps that set lo and hi; the band is
+  // then gathered from those words (scatter_band_members) instead of with two compares per element.
+  constexpr bool PACKS = scatter_gathers(E);
+  constexpr int PW = (E + 31) / 32;
+  uint32_t last[PW], below_lo[PW], below_hi[PW];
+  bool lo_moved = false, hi_moved = false;
   auto count = [&](float t) -> int {
     if constexpr (KEEP) {
       return count_ge<E, NEG>(x, t, m);
+    } else if constexpr (PACKS) {
+      lane_below_packs<E, NEG>(x, t, last);
+      uint32_t below = 0;
+#pragma unroll
+      for (int g = 0; g < PW; ++g) below += (uint32_t)__builtin_popcount(last[g]);
+      return E * kWave - wave_sum((int)below);
     } else {
       return count_ge_wide<E, ACC, NEG>(x, t);
+    }
+  };
+  auto note_bound = [&](int cnt) {  // after move_bound with the latest count
+    if constexpr (PACKS) {
+      if (cnt < k) {  // uniform
+        hi_moved = true;
+#pragma unroll
+        for (int g = 0; g < PW; ++g) below_hi[g] = last[g];
+      } else {
+        lo_moved = true;
+#pragma unroll
+        for (int g = 0; g < PW; ++g) below_lo[g] = last[g];
+      }
+    }
+  };
+  auto gather = [&](float (&band)[BR]) -> int {  // the band [lo, hi) into band[]; returns #{key >= hi}
+    if constexpr (PACKS) {
+      if (!lo_moved) lane_below_packs<E, NEG>(x, lo, below_lo);  // a bound still at the row's minimum or maximum
+      if (!hi_moved) lane_below_packs<E, NEG>(x, hi, below_hi);
+      int above = 0;
+      uint32_t members = 0;
+      scatter_band_members<E, NEG>(x, below_lo, below_hi, lane, stage_addr + (uint32_t)(BR * kWave) * 4u,
+                                   [&](uint32_t n, uint32_t ab) -> uint32_t {
+                                     above = (int)ab;
+                                     members = n <= (uint32_t)(BR * kWave) ? n : 0u;
+                                     return n <= (uint32_t)(BR * kWave) ? stage_addr : kNoRoom;
+                                   });
+      load_band<NEG, BR>(stage_addr, lane, members, band);
+      return above;
+    } else {
+      uint32_t nb;
+      return gather_band<E, NEG, false, BR>(x, lo, hi, lane, stage_addr, band, nb);
     }
   };
   if constexpr (MODE == kExact) {
@@ -688,6 +830,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
         }
         move_bound(lo, hi, thres, cnt, k);
         if constexpr (NARROW) {
+          note_bound(cnt);
           cnt_lo = cnt < k ? cnt_lo : cnt;
           cnt_hi = cnt < k ? cnt : cnt_hi;
           if (cnt_lo - cnt_hi <= BR * kWave) {
@@ -703,6 +846,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
         }
         move_bound(lo, hi, thres, cnt, k);
         if constexpr (NARROW) {
+          note_bound(cnt);
           cnt_lo = cnt < k ? cnt_lo : cnt;
           cnt_hi = cnt < k ? cnt : cnt_hi;
           if (cnt_lo - cnt_hi <= BR * kWave) {
@@ -714,8 +858,7 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       if constexpr (NARROW) {
         if (narrow) {
           float band[BR];
-          uint32_t nb;
-          const int above = gather_band<E, NEG, false, BR>(x, lo, hi, lane, stage_addr, band, nb);
+          const int above = gather(band);
           int unused_steps = 0;
           search_band<kExact, NEG, DT, BR>(band, above, k, 0.0f, lo, hi, thres, hit, unused_steps);
         }
@@ -763,11 +906,11 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
       move_bound(lo, hi, thres, cnt, k);
       if constexpr (NARROW) {
         if (!narrow) {
+          note_bound(cnt);
           cnt_lo = cnt < k ? cnt_lo : cnt;
           cnt_hi = cnt < k ? cnt : cnt_hi;
           if (cnt_lo - cnt_hi <= BR * kWave) {
-            uint32_t nb;
-            above = gather_band<E, NEG, false, BR>(x, lo, hi, lane, stage_addr, band, nb);
+            above = gather(band);
             narrow = true;
           }
         }
@@ -804,12 +947,13 @@ __device__ __forceinline__ int select_row(const float (&xin)[G * NG], int lane, 
         if (cnt == k) break;
         if constexpr (NARROW) {
           if (!narrow) {
+            note_bound(cnt);
             cnt_lo = cnt < k ? cnt_lo : cnt;
             cnt_hi = cnt < k ? cnt : cnt_hi;
-            // the gather costs about as much as three full-width steps: only when more remain
-            if (cnt_lo - cnt_hi <= BR * kWave && it + 6 < max_iter) {
-              uint32_t nb;
-              above = gather_band<E, NEG, false, BR>(x, lo, hi, lane, stage_addr, band, nb);
+            // the gather costs about as much as three full-width steps (one, from sign-bit words): only
+            // when more remain
+            if (cnt_lo - cnt_hi <= BR * kWave && it + (PACKS ? 2 : 6) < max_iter) {
+              above = gather(band);
               narrow = true;
             }
           }
@@ -941,8 +1085,10 @@ __device__ __forceinline__ void store_streaming(uint32_t* p, uint32_t v) {
   asm volatile("global_store_dword %0, %1, off " RTOPK_STORE_POLICY : : "v"(p), "v"(v) : "memory");
 }
 
+// (Rows of 128 values per lane are held to three wavefronts per SIMD and rows of 96 to four: the ragged-width variants would
+// otherwise take a few registers more than that allows and run two.)
 template <int G, int NG, int R, bool FULL, int MODE, bool NEG, typename IdxT, int DT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(G * NG >= 128 ? 3 : (G * NG >= 96 ? 4 : 1))))
     rtopk_wave_kernel(const void* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
                       void* __restrict__ out_vals, IdxT* __restrict__ out_idx, int32_t* __restrict__ out_iters,
                       int vec_store) {
@@ -958,7 +1104,7 @@ __global__ void __launch_bounds__(256)
   const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
   // per wavefront: R*k pairs, and at least the band scratch where the exact search of a wide row uses it
   static_assert(!narrows(E, MODE) || R == 1, "the band scratch reuses the staging area of the wavefront's only row");
-  constexpr int kMinPairs = narrows(E, MODE) ? band_regs(E) * kWave / 2 : 0;
+  constexpr int kMinPairs = band_scratch_floats(E) / 2;
   const int pairs_per_wave = R * k > kMinPairs ? R * k : kMinPairs;
   uint2* stage = stage_all + (size_t)wave * pairs_per_wave;
 
@@ -1066,7 +1212,7 @@ __global__ void __launch_bounds__(256)
   const int64_t r0 = ((int64_t)blockIdx.x * waves_per_block + wave) * R;
   if (r0 >= N) return;
   const int nrows = (N - r0 < R) ? (int)(N - r0) : R;
-  uint2* scratch = band_scratch + (size_t)wave * (band_regs(E) * kWave / 2);
+  uint2* scratch = band_scratch + (size_t)wave * (band_scratch_floats(E) / 2);
 
   float x[R][E];
 #pragma unroll
@@ -1106,7 +1252,7 @@ hipError_t launch_dense(const LaunchArgs& a) {
   const int64_t batches = (a.N + R - 1) / R;
   const int64_t blocks = (batches + waves - 1) / waves;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  const size_t lds = narrows(G * NG, MODE) ? (size_t)waves * band_regs(G * NG) * kWave * sizeof(float) : 0;
+  const size_t lds = (size_t)waves * band_scratch_floats(G * NG) * sizeof(float);
   return launch_kernel(rtopk_dense_kernel<G, NG, R, FULL, MODE>, dim3((unsigned)blocks), dim3(waves * kWave), lds,
                        a.stream, static_cast<const float*>(a.in), a.N, a.M, a.k, a.max_iter,
                        static_cast<float*>(a.out_vals));
@@ -1119,7 +1265,7 @@ hipError_t launch(const LaunchArgs& a) {
   // LDS per wavefront: R*k staged pairs of 8 bytes; at most 64 KiB per block.
   size_t per_wave = (size_t)R * (size_t)a.k * sizeof(uint2);
   // the exact search of wide rows gathers its band through the (not yet used) staging area
-  if (narrows(G * NG, MODE) && per_wave < band_regs(G * NG) * kWave * sizeof(float)) per_wave = band_regs(G * NG) * kWave * sizeof(float);
+  if (per_wave < band_scratch_floats(G * NG) * sizeof(float)) per_wave = band_scratch_floats(G * NG) * sizeof(float);
   // one wavefront per workgroup, except where a wavefront stages 8 KiB or more of pairs: there four
   // per workgroup measured 7 % faster (2^20 x 256, k = 128: 387 -> 360 us), while at 4 KiB and below
   // one per workgroup is the faster by 3-11 %
