@@ -150,11 +150,29 @@ __device__ __forceinline__ void store_pair_if_below(uint32_t pos, uint32_t limit
 // at 8 wavefronts per workgroup, two rows per compute unit.  Forcing 80 registers (a third row per
 // compute unit, at the price of 5 spilled registers) measured no faster in exact mode and 7-15 % slower
 // with early stopping, so the allocation is left to the compiler.
+// Groups of a row that a workgroup loads ahead, during the ranking of its previous row (16-wavefront
+// shape only: the others are launched with one workgroup per row): RTOPK_BLOCK_AHEAD values per lane,
+// half of the row, which is what the register budget of four wavefronts per SIMD leaves free (not the
+// scalar-load fallback, whose ranking by lane masks needs those registers).
+#ifndef RTOPK_BLOCK_AHEAD
+#define RTOPK_BLOCK_AHEAD 32
+#endif
+// (Measured on 1 GiB inputs: 4096 x 65536 exact 357 us with a workgroup per row, 347 us looping, 319 us with
+// 32 values loaded ahead, 324 us with 24, 361 us with 40, which spills.  The narrower shapes, which have two
+// to four workgroups on a compute unit whose phases overlap anyway, lose: 8192 x 32768 247 -> 278 us,
+// 16384 x 16384 249 -> 299 us when each resident workgroup walks a fixed share of the rows.)
+#ifndef RTOPK_BLOCK_PERSIST_MIN_W
+#define RTOPK_BLOCK_PERSIST_MIN_W 16
+#endif
+constexpr bool block_persistent(int W) { return W >= RTOPK_BLOCK_PERSIST_MIN_W; }
+constexpr int block_groups_ahead(int W, int G) { return block_persistent(W) && G > 1 ? RTOPK_BLOCK_AHEAD / G : 0; }
+
 // One row, by the whole workgroup.  Every wavefront leaves through the same return statement.
 template <int G, int NG, int W, int MODE, bool NEG, int DT, bool DENSE>
 __device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in, int64_t N, int M, int k, int max_iter,
                                           float eps_rel, void* __restrict__ out_vals, int32_t* __restrict__ out_idx,
-                                          int32_t* __restrict__ out_iters) {
+                                          int32_t* __restrict__ out_iters, int64_t r_next, bool& have_ahead,
+                                          float (&ahead)[block_groups_ahead(W, G) * G + 1]) {
   static_assert(!DENSE || DT == kF32, "the dense form is built for fp32 rows");
   constexpr int E = G * NG;
   constexpr int T = NG * W;  // (group, wavefront) cells of a row, in column order
@@ -170,17 +188,25 @@ __device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in
   __shared__ float s_res[3];
   __shared__ int s_resi[2];
 
-  const int lane = threadIdx.x & (kWave - 1);
+  int lane = threadIdx.x & (kWave - 1);
+  asm volatile("" : "+v"(lane));  // opaque per row: nothing derived from it is carried around the loop over rows
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const ElemT* row = static_cast<const ElemT*>(in) + r * (int64_t)M;
 
   // Loading stage.  Lanes past M load the row's first columns (in bounds, cannot change min or max).
+  // The first groups may have been loaded already, while the workgroup's previous row was ranked.
+  constexpr int AHEAD = block_groups_ahead(W, G) < NG ? block_groups_ahead(W, G) : NG;
   float x[E];
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     const int col0 = ((g * W + wave) * kWave + lane) * G;
     float v[G];
-    load_group<DT, G>(row, col0 < M ? col0 : 0, v);
+    if (g < AHEAD && have_ahead) {  // uniform
+#pragma unroll
+      for (int c = 0; c < G; ++c) v[c] = ahead[g * G + c];
+    } else {
+      load_group<DT, G>(row, col0 < M ? col0 : 0, v);
+    }
 #pragma unroll
     for (int c = 0; c < G; ++c) x[g * G + c] = v[c];
   }
@@ -379,6 +405,7 @@ __device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in
     // (Counting the midpoint and both midpoints that can follow it in one pass -- two levels per barrier,
     // three counts per element -- gives the same bounds but measured slower, 250 -> 276 us at eight steps on
     // 8192 x 32768: a step is bound by its counting work, not by the barrier.)
+#pragma nounroll
     for (int it = 0; it < max_iter; ++it) {
       const float thres = (lo + hi) * 0.5f;
       const int cnt = count(thres);
@@ -386,6 +413,23 @@ __device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in
       if (cnt == k) break;
     }
     tA = lo;
+  }
+  // The search is over; what follows needs few registers besides the row.  A workgroup that has another
+  // row to do starts that row's first loads now, so that they fly while this row is ranked and stored.
+  have_ahead = false;
+  if constexpr (AHEAD > 0) {
+    if (r_next < N) {
+      const ElemT* next = static_cast<const ElemT*>(in) + r_next * (int64_t)M;
+#pragma unroll
+      for (int g = 0; g < AHEAD; ++g) {
+        const int col0 = ((g * W + wave) * kWave + lane) * G;
+        float v[G];
+        load_group<DT, G>(next, col0 < M ? col0 : 0, v);
+#pragma unroll
+        for (int c = 0; c < G; ++c) ahead[g * G + c] = v[c];
+      }
+      have_ahead = true;
+    }
   }
   const bool has_b = limB > 0;  // uniform over the workgroup
 
@@ -473,6 +517,9 @@ __device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in
     // candidates in the group.  A lane's non-candidates get rank 0xffffffff, so that the one compare against
     // limA (which also keeps every store inside the row's k slots whatever the input held) decides who
     // stores.  Cells without a candidate are skipped as a whole.
+    // (opaque copies: otherwise the group fields extracted in part 1 are kept in 16 registers for reuse here)
+#pragma unroll
+    for (int i = 0; i < (E + 31) / 32; ++i) asm volatile("" : "+v"(cand[i]));
     // lane g fetches the prefix of cell g: one LDS round trip for all the wavefront's cells
     const int my_cell = s_tab[0][(lane < NG ? lane : 0) * W + wave];
 #pragma unroll
@@ -592,12 +639,22 @@ __device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in
 // shape (16 wavefronts, one workgroup to a compute unit) is launched with one workgroup per compute unit
 // instead, which saves the dispatch of a new 1024-thread workgroup between a unit's rows.
 template <int G, int NG, int W, int MODE, bool NEG, int DT, bool DENSE>
-__global__ void __launch_bounds__(W * kWave)
+__global__ void __launch_bounds__(W * kWave) __attribute__((amdgpu_waves_per_eu(block_persistent(W) ? 4 : 1)))
     rtopk_block_kernel(const void* __restrict__ in, int64_t N, int M, int k, int max_iter, float eps_rel,
                        void* __restrict__ out_vals, int32_t* __restrict__ out_idx, int32_t* __restrict__ out_iters) {
-  for (int64_t r = blockIdx.x; r < N; r += gridDim.x) {
-    block_row<G, NG, W, MODE, NEG, DT, DENSE>(r, in, N, M, k, max_iter, eps_rel, out_vals, out_idx, out_iters);
-    __syncthreads();  // the next row reuses the shared tables
+  bool have_ahead = false;
+  float ahead[block_groups_ahead(W, G) * G + 1];
+  if constexpr (block_persistent(W)) {
+    for (int64_t r = blockIdx.x; r < N; r += gridDim.x) {
+      block_row<G, NG, W, MODE, NEG, DT, DENSE>(r, in, N, M, k, max_iter, eps_rel, out_vals, out_idx, out_iters,
+                                                r + gridDim.x, have_ahead, ahead);
+      __syncthreads();  // the next row reuses the shared tables
+    }
+  } else {
+    const int64_t r = blockIdx.x;  // launched with one workgroup per row
+    if (r < N)
+      block_row<G, NG, W, MODE, NEG, DT, DENSE>(r, in, N, M, k, max_iter, eps_rel, out_vals, out_idx, out_iters, N,
+                                                have_ahead, ahead);
   }
 }
 
@@ -621,9 +678,9 @@ template <int G, int NG, int W, int MODE, bool NEG = false, int DT = kF32, bool 
 hipError_t launch_block(const LaunchArgs& a) {
   if (a.N > 0x7fffffffLL) return hipErrorInvalidConfiguration;
   int64_t grid = a.N;
-  if (RTOPK_BLOCK_PERSIST && W == 16) {
-    const int units = compute_units();
-    if (units > 0 && grid > units) grid = units;
+  if (RTOPK_BLOCK_PERSIST && block_persistent(W)) {
+    const int64_t resident = (int64_t)compute_units() * (16 / W);  // workgroups that run at the same time
+    if (resident > 0 && grid > resident) grid = resident;
   }
   return launch_kernel(rtopk_block_kernel<G, NG, W, MODE, NEG, DT, DENSE>, dim3((unsigned)grid), dim3(W * kWave), 0,
                        a.stream, a.in, a.N, a.M, a.k, a.max_iter, a.eps_rel, a.out_vals,
