@@ -1,5 +1,6 @@
-"""GPU parity for rows wider than 65536 columns (one workgroup per row, the row read several times, eight
-bisection steps per pass): indices and values bit-exact against the CPU oracle in every mode."""
+"""GPU parity for rows wider than 65536 columns (one workgroup per row, the row streamed: once when the pass
+for its minimum and maximum can also keep the candidates, else with eight bisection steps per further pass):
+indices and values bit-exact against the CPU oracle in every mode."""
 import numpy as np
 import pytest
 
@@ -101,6 +102,28 @@ def test_streamed_rows_whose_candidates_crowd_one_part_of_the_row():
     x = np.stack([base, base[::-1].copy(), np.roll(base, 12345)]).astype(np.float32)
     for k in (100, 129, 2048, 2049):
         check(R, x, k, f"sorted k={k}", modes=("exact", "early"))
+
+
+def test_streamed_rows_skewed_values_outliers_and_k_near_the_list_capacity():
+    # the pass that finds minimum and maximum also keeps the keys above a rising floor, chosen from 256 equal
+    # parts of the range seen so far: heavy skew, one huge outlier (every other key in the lowest part) and a
+    # range that spans many binades put that choice under stress; k around a thousand fills the lists; every
+    # case must come out the same whether the lists are used or the search passes take over
+    R = _gpu()
+    M = 150000
+    rng = np.random.default_rng(2024)
+    g = rng.standard_normal((6, M)).astype(np.float32)
+    x = np.empty((6, M), dtype=np.float32)
+    x[0] = np.exp(8.0 * g[0])            # lognormal over ~28 binades
+    x[1] = -np.exp(8.0 * g[1])           # the same, all negative
+    x[2] = g[2]
+    x[2, 77777] = 3.0e38                 # one outlier near the top of the format
+    x[3] = g[3]
+    x[3, 5] = -3.0e38                    # and one at the bottom
+    x[4] = np.where(g[4] > 0, 1.0e-30 * g[4], g[4])   # positive side squeezed into tiny values
+    x[5] = np.floor(g[5] * 2.0) / 2.0    # a few dozen distinct values
+    for k in (3, 512, 1000, 1365, 1366, 2047):
+        check(R, x, k, f"skewed k={k}", modes=("exact", "early", "eps", "smallest"))
 
 
 def test_streamed_rows_many_rows_guard_bands_and_nonfinite_inputs():

@@ -37,12 +37,9 @@ def test_profile_summary_parses_and_is_self_consistent(path):
         rd, wr, tot, algo = (int(v.replace(",", "")) for v in (rd, wr, tot, algo))
         assert abs(rd + wr - tot) <= 2
         assert abs(tot / algo - float(ratio)) < 1e-3
-        if "rtopk_stream_kernel" in os.path.basename(path):
-            # rows too wide to hold on chip are read once for min/max, once per eight search steps and once to
-            # write the result: three to four times the algorithmic bytes by design
-            assert 2.8 < tot / algo < 4.3
-        else:
-            assert 0.9 < tot / algo < 1.15, "measured traffic far from the algorithmic bytes: re-reads or a stale summary"
+        # (also for rows too wide to hold on chip: on this workload the streamed kernel finds its k pairs in
+        # the pass that finds the row's minimum and maximum, so it too reads a row once)
+        assert 0.9 < tot / algo < 1.15, "measured traffic far from the algorithmic bytes: re-reads or a stale summary"
     # no derived percentage above 100
     for pct in re.findall(r"\((\d+) %\)", text):
         assert int(pct) <= 100, "a utilisation above 100 % is a normalisation error"
