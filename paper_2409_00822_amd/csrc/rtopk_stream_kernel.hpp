@@ -1,23 +1,28 @@
 // Row-wise top-k for rows that no longer fit a workgroup's registers (65536 < M <= 2^24): one workgroup
-// per row, the row streamed from memory several times.
+// per row, the row streamed from memory -- once in the usual case.
 //
 // Same method and same results as the other kernels (RTop-K, arXiv 2409.00822, Section 3.1, Algorithms 1
 // and 2).  Appendix B of the paper observes that for very wide rows a search that pays one pass over the
-// row per bisection step loses to radix-style selection.  The remedy here keeps the paper's thresholds
-// and takes kLevels = 8 bisection steps per pass instead of one: all 255 midpoints that the next eight
-// steps can possibly visit are fixed by (lo, hi) alone -- they form a binary tree, each node the fp32
-// midpoint of its interval exactly as the algorithms compute it -- so one pass sorts every element of
-// the band [lo, hi) into the 256 leaf intervals of that tree (an arithmetic guess corrected against a table
-// in LDS, one LDS atomic), and the suffix sums of that histogram are the counts cnt(t) of all 255
-// thresholds at once.  The eight steps are then replayed on the counts, with the algorithms' own guards
-// (cnt == k, the iteration limit, epsilon, the midpoint no longer strictly inside), bit for bit as the
-// one-step-per-pass loop would have run them.  In effect: a radix-256 select over the value range whose
-// digit boundaries are the paper's midpoints.  A row costs one pass for its minimum and maximum and one
-// pass per eight search steps (one for Algorithm 2 with max_iter <= 8, two for a typical exact search).
-// The last search pass also leaves, in LDS, every key that can still be selected, with its column; the k
-// pairs are ranked and written from those lists.  Only when a list overflows (k in the thousands, or the
-// winners crowded into one part of the row) or the lists cannot be shown to be complete is the row read
-// once more to rank and write.
+// row per bisection step loses to radix-style selection.  Two remedies here keep the paper's thresholds.
+//
+// First: the algorithms look at a count only to compare it with k.  The pass that finds the row's minimum
+// and maximum (needed before the first threshold) therefore also keeps, in LDS, every key at or above a
+// floor that it raises as it goes, chosen so that more than k keys stay at or above it.  Counts over those
+// keys decide every step exactly as counts over the row would, so the whole search runs on them, and the
+// k pairs are written from them: one pass over the row.
+//
+// Second, for rows whose kept keys do not fit (k in the thousands, or the winners crowded into one part
+// of the row) or whose search stops so early that its last threshold lies below the floor: kLevels = 8
+// bisection steps per pass instead of one.  All 255 midpoints that the next eight steps can possibly visit
+// are fixed by (lo, hi) alone -- they form a binary tree, each node the fp32 midpoint of its interval
+// exactly as the algorithms compute it -- so one pass sorts every element of the band [lo, hi) into the 256
+// leaf intervals of that tree (an arithmetic guess corrected against a table in LDS, one LDS atomic), and
+// the suffix sums of that histogram are the counts cnt(t) of all 255 thresholds at once.  The eight steps
+// are then replayed on the counts, with the algorithms' own guards (cnt == k, the iteration limit,
+// epsilon, the midpoint no longer strictly inside), bit for bit as the one-step-per-pass loop would have
+// run them.  In effect: a radix-256 select over the value range whose digit boundaries are the paper's
+// midpoints.  The last such pass again leaves the keys that can still be selected in LDS for the final
+// write; only if those lists overflow as well is the row read once more to rank and write.
 //
 // Layout: wavefront w of 16 walks the w-th sixteenth of the row, lane l owning G consecutive columns of
 // each 64*G-column load (G = 4: 128-bit loads), so that a wavefront meets its columns in ascending order.
