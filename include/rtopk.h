@@ -31,9 +31,11 @@
  *  - Limits: 1 <= k <= M <= rtopk_max_m() = 2^24 for fp32 rows with int32 columns (65536 for rows stored
  *    in 16 bits, the dense form and the backward edge; 256 in the *_u8 variants); 0 <= N; N * M and
  *    N * k must fit in int64_t.  Rows wider than 8192 columns are handled by one workgroup per row, and
- *    then N < 2^31.  Rows wider than 65536 columns are not held on chip but read several times (once for
- *    the minimum and maximum, once per eight search steps, once to write the result), and a launch of
- *    fewer such rows than the GPU has compute units leaves the others idle.
+ *    then N < 2^31.  Rows wider than 65536 columns are not held on chip but streamed from memory: once
+ *    when k is up to about a thousand and the winners are not crowded into one sixteenth of the row,
+ *    otherwise once for the minimum and maximum, once per eight search steps and, for k in the
+ *    thousands, once more to write the result; a launch of fewer such rows than twice the number of
+ *    compute units leaves some of them idle.
  */
 #ifndef RTOPK_H_
 #define RTOPK_H_
