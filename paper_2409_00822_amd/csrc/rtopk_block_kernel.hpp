@@ -287,7 +287,11 @@ __device__ __forceinline__ void block_row(int64_t r, const void* __restrict__ in
     int steps = 0, cnt_lo = M, cnt_hi = 0;
     const float eps = MODE == kEps ? eps_rel * __builtin_fabsf(hi) : 0.0f;
     // (Narrowing as soon as the band fits stays the fastest: never narrowing costs 3 % on Laplace rows --
-    // 12.3 full-width steps on average at 32768 columns -- and starting only after 8 to 14 steps 7-12 %.)
+    // 12.3 full-width steps on average at 32768 columns -- and starting only after 8 to 14 steps 7-12 %.
+    // Narrowing three to four steps earlier, onto kBandRegs registers per lane of EVERY wavefront with the
+    // remaining steps still going through the barrier, measured slower as well: 8192 x 32768 249 -> 263 us,
+    // 4096 x 65536 319 -> 350 us; a step on one wavefront's registers costs a tenth of a step that all
+    // wavefronts have to meet for.)
     // the sign-bit words of the steps that set the current lo and hi: the gather needs no compare of its own
     uint32_t below_lo[kPackWords], below_hi[kPackWords];
     bool lo_moved = false, hi_moved = false;
