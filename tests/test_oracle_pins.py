@@ -501,3 +501,37 @@ def test_eps_collection_reading_against_the_printed_branch(eps_rel):
         assert (rv.min(axis=1) >= pv.min(axis=1)).all()
         assert (rv.sum(axis=1, dtype=np.float64) >= pv.sum(axis=1, dtype=np.float64) - 1e-9).all()
         print(f"eps'={eps_rel} {gen}: selections differ on {differ * 100:.2f} % of rows")
+
+
+# --------------------------------------------------------------------------------------------
+# the search only compares counts with k: a property the kernel for very wide rows relies on
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("gen", ["normal", "laplace", "ties", "ints"])
+def test_keys_below_a_floor_with_more_than_k_keys_above_it_never_matter(gen):
+    # Let T0 be any value with #{x >= T0} > k.  For a threshold t <= T0 the count is then > k whatever lies
+    # below T0, and for t > T0 nothing below T0 is counted; Alg. 1 and Alg. 2 branch on cnt < k, cnt == k,
+    # cnt > k only.  So moving every element below T0 down to the row's minimum (which keeps min and max,
+    # hence every midpoint) must change neither the exit iteration nor, once the search has run to its
+    # end, the selection.  (The kernel for rows wider than 65536 columns keeps only the keys above such a
+    # floor while it looks for the minimum and maximum, and searches those.)
+    N, M = 60, 3000
+    x = {"normal": lambda: workloads.normal(N, M, seed=1501), "laplace": lambda: workloads.laplace(N, M, seed=1502),
+         "ties": lambda: workloads.normal_ties(N, M, seed=1503, p=0.4),
+         "ints": lambda: workloads.small_ints(N, M, seed=1504, span=40)}[gen]()
+    for k in (1, 17, 256):
+        desc = -np.sort(-x, axis=1)
+        for margin in (1, 8, 300):
+            floor = desc[:, k + margin - 1:k + margin]          # at least k + margin keys are >= floor
+            y = np.where(x >= floor, x, x.min(axis=1, keepdims=True)).astype(np.float32)
+            assert (np.sum(y >= floor, axis=1) > k).all()
+            ev, ei, et = oracle.alg1(x, k, eps_rel=0.0)
+            fv, fi, ft = oracle.alg1(y, k, eps_rel=0.0)
+            assert np.array_equal(et, ft), (gen, k, margin, "exit iterations")
+            assert np.array_equal(ei, fi) and np.array_equal(bits(ev), bits(fv)), (gen, k, margin, "selection")
+            for eps in (1e-3, 0.2):
+                _, _, et = oracle.alg1(x, k, eps_rel=eps, want_select=False)
+                _, _, ft = oracle.alg1(y, k, eps_rel=eps, want_select=False)
+                assert np.array_equal(et, ft), (gen, k, margin, eps)
+            av, ai = oracle.topk_earlystop(x, k, 512)
+            bv, bi = oracle.topk_earlystop(y, k, 512)
+            assert np.array_equal(ai, bi) and np.array_equal(bits(av), bits(bv)), (gen, k, margin, "Alg. 2 at its fixed point")
