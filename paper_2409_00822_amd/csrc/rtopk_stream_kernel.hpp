@@ -43,11 +43,8 @@ constexpr int kLeaves = 1 << kLevels;
 #ifndef RTOPK_STREAM_WAVES_PER_SIMD
 #define RTOPK_STREAM_WAVES_PER_SIMD 8
 #endif
-#ifndef RTOPK_STREAM_RAISE_FACTOR
-#define RTOPK_STREAM_RAISE_FACTOR 2
-#endif
 #ifndef RTOPK_STREAM_AHEAD
-#define RTOPK_STREAM_AHEAD 2
+#define RTOPK_STREAM_AHEAD 3
 #endif
 constexpr int kKeptPerWave = 256;  // at least one load of a wavefront (the first, which nothing filters yet)
 
@@ -110,15 +107,22 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
   const int units = (M + kUnit - 1) / kUnit;
   const int u0 = (int)((int64_t)units * wave / kStreamWaves), u1 = (int)((int64_t)units * (wave + 1) / kStreamWaves);
   const int trips = (units + kStreamWaves - 1) / kStreamWaves;  // no wavefront has more loads than this
-  constexpr int kAhead = RTOPK_STREAM_AHEAD;  // loads of a wavefront in flight while the previous kAhead are worked on (one at
-                             // a time leaves a pass bound by memory latency: 16 KiB in flight per compute unit)
-  auto load_ahead = [&](int i, float (&q)[kAhead][G]) {
-#pragma unroll
-    for (int j = 0; j < kAhead; ++j) {
-      const int u = u0 + i + j;
-      const int c0 = u * kUnit + lane * G;
-      if (u < u1 && c0 < M) stream_load<G>(row + c0, q[j]);
-    }
+  // A wavefront keeps kAhead loads in flight in a ring of registers: a slot is worked on, then loaded again
+  // with the wavefront's load kAhead further on (with one load at a time a pass is bound by memory latency).
+  constexpr int kAhead = RTOPK_STREAM_AHEAD;
+  auto load_slot = [&](int i, float (&slot)[G]) {  // the wavefront's i-th load
+    // (no branch: past the wavefront's share or the row's end the row's first columns are loaded and not
+    // looked at; a conditional load would make the compiler wait for all loads in flight at every use)
+    const int u = u0 + i;
+    const int c0 = u * kUnit + lane * G;
+    stream_load<G>(row + ((u < u1 && c0 < M) ? c0 : 0), slot);
+  };
+  // The same with the non-temporal hint, for pass 0: as a rule the row is not read again, and streaming
+  // loads that do not displace each other's lines from the caches run faster (see rtopk_kernel.hpp).
+  auto load_slot_once = [&](int i, float (&slot)[G]) {
+    const int u = u0 + i;
+    const int c0 = u * kUnit + lane * G;
+    load_group<kF32, G>(row, (u < u1 && c0 < M) ? c0 : 0, slot);
   };
   uint2* kept = &s_kept[wave][0];
   if (tid < 2 * kLeaves) s_parts[tid >> kLevels][tid & (kLeaves - 1)] = 0;  // the third is cleared by the first raise
@@ -268,25 +272,22 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
         if (!void0) n0 = n_new;
       }
     };
-    int next_raise = kAhead;
-    float cur[kAhead][G], nxt[kAhead][G];
-    load_ahead(0, cur);
-    for (int i = 0; i < trips; i += kAhead) {  // i, trips and next_raise are uniform over the workgroup
-      if (i + kAhead < trips) load_ahead(i + kAhead, nxt);
-      // the floor is raised after 1, 2, 4, 8, ... loads: after the first load of the first group (nothing
-      // filters that load: the list is full of it), then at the end of the groups that complete those numbers
-      take(cur[0], u0 + i);
-      if (i == 0 && trips > 1) raise_floor();
+    // The floor is raised after 1, 2, 4, 8, ... loads per wavefront: after the first (nothing filters that
+    // load, so the list is full of it), and so on; i, j, trips and next_raise are uniform over the workgroup.
+    int next_raise = 2;
+    float ring[kAhead][G];
 #pragma unroll
-      for (int j = 1; j < kAhead; ++j) take(cur[j], u0 + i + j);
-      if (i + kAhead == next_raise && i + kAhead < trips) {
-        next_raise *= RTOPK_STREAM_RAISE_FACTOR;
-        raise_floor();
-      }
+    for (int j = 0; j < kAhead; ++j) load_slot_once(j, ring[j]);
+    for (int i = 0; i < trips; i += kAhead) {
 #pragma unroll
       for (int j = 0; j < kAhead; ++j) {
-#pragma unroll
-        for (int c = 0; c < G; ++c) cur[j][c] = nxt[j][c];
+        take(ring[j], u0 + i + j);
+        load_slot_once(i + j + kAhead, ring[j]);
+        const int done = i + j + 1;
+        if (done < trips && (done == 1 || done == next_raise)) {
+          if (done > 1) next_raise *= 2;
+          raise_floor();
+        }
       }
     }
     float wmax, wmin;
@@ -577,24 +578,21 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
       }
       n_kept += total;
     };
-    float cur[kAhead][G], nxt[kAhead][G];
-    load_ahead(0, cur);
-    for (int i = 0; i < trips; i += kAhead) {  // i, trips and next_sync are uniform over the workgroup
-      if (i + kAhead < trips) load_ahead(i + kAhead, nxt);
-      // bstar is raised after 1, 4, 16, ... loads: after the first load of the first group (nothing filters
-      // that load, so the list is full of it), then at the end of the groups that complete those numbers
-      process(cur[0], u0 + i);
-      if (i == 0 && trips > 1) raise_bstar();
+    // bstar is raised after 1, 4, 16, ... loads per wavefront (after the first because nothing filters that
+    // load, so the list is full of it); i, j, trips and next_sync are uniform over the workgroup.
+    float ring[kAhead][G];
 #pragma unroll
-      for (int j = 1; j < kAhead; ++j) process(cur[j], u0 + i + j);
-      if (i + kAhead == next_sync && i + kAhead < trips) {
-        next_sync *= 4;
-        raise_bstar();
-      }
+    for (int j = 0; j < kAhead; ++j) load_slot(j, ring[j]);
+    for (int i = 0; i < trips; i += kAhead) {
 #pragma unroll
       for (int j = 0; j < kAhead; ++j) {
-#pragma unroll
-        for (int c = 0; c < G; ++c) cur[j][c] = nxt[j][c];
+        process(ring[j], u0 + i + j);
+        load_slot(i + j + kAhead, ring[j]);
+        const int done = i + j + 1;
+        if (done < trips && (done == 1 || done == next_sync)) {
+          if (done > 1) next_sync *= 4;
+          raise_bstar();
+        }
       }
     }
     count_pending();
