@@ -147,14 +147,15 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
   {
     float mx = -__builtin_inff(), nm = -__builtin_inff();
     auto take = [&](const float (&v)[G], int u) {  // one load of the wavefront, already in registers
-      if (u >= u1) return;  // uniform over the wavefront
+      // No branch before the one that skips the list: every branch between a load's issue and its use
+      // makes the compiler wait for all loads in flight instead of this one.
       const int c0 = u * kUnit + lane * G;
-      const bool valid = c0 < M;
+      const bool valid = u < u1 && c0 < M;
       bool keep[G], any_keep = false;
 #pragma unroll
       for (int c = 0; c < G; ++c) {
-        mx = valid ? vmax(mx, v[c]) : mx;
-        nm = valid ? vmax_an(nm, v[c]) : nm;
+        mx = vmax(mx, valid ? v[c] : -__builtin_inff());
+        nm = vmax_an(nm, valid ? v[c] : __builtin_inff());
         keep[c] = valid && keyof<NEG>(v[c]) >= T0;
         any_keep = any_keep || keep[c];
       }
