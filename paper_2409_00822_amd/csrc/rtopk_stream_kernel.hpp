@@ -538,6 +538,8 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
     };
     // One load of the wavefront (64 * G columns from unit u on), already in registers.
     auto process = [&](const float (&v)[G], int u) {
+      // (this early exit makes the compiler wait for all loads in flight here; leaving it out, as pass 0
+      // does, costs this pass registers it does not have: 18 spill, 1024 x 262144 with k = 2000 700 -> 779 us)
       if (u >= u1) return;  // uniform over the wavefront
       const int c0 = u * kUnit + lane * G;
       const bool valid = c0 < M;
@@ -552,9 +554,6 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
       }
       // once bstar has risen most loads of a wavefront hold no such key at all: one scalar branch
       if (__builtin_amdgcn_ballot_w64(any_keep) == 0) return;
-#ifdef RTOPK_STREAM_PROBE_NOAPPEND
-      if (u > u0) return;
-#endif
       uint64_t m[G];
       uint32_t pos = 0, total = 0;
 #pragma unroll
