@@ -76,7 +76,7 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
   __shared__ int s_void[kStreamWaves];    // per wavefront: its list of pass 0 ran full
   __shared__ int s_cnt[2][kStreamWaves];  // per-wavefront counts of a search step on the lists, double buffered
   __shared__ int s_pre[2][kStreamWaves];  // per-wavefront candidate counts of a chunk (A in the low half, B in the high), double buffered
-  __shared__ uint2 s_kept[kStreamWaves][kKeptPerWave];  // per wavefront: (value bits, column) of the keys at or above bstar met by a search pass
+  __shared__ uint2 s_kept[kStreamWaves][kKeptPerWave];  // per wavefront, in column order: (value bits, column) of the keys at or above the floor of pass 0, later at or above bstar of a search pass
 
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
