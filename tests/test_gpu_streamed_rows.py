@@ -126,6 +126,27 @@ def test_streamed_rows_skewed_values_outliers_and_k_near_the_list_capacity():
         check(R, x, k, f"skewed k={k}", modes=("exact", "early", "eps", "smallest"))
 
 
+def test_streamed_rows_at_the_maximum_width():
+    # M = rtopk_max_m() = 2^24 columns (64 MiB per row): column numbers use 24 bits, a wavefront makes 4096
+    # loads, the floor of the first pass is raised 12 times; small k from the lists, k = 5000 through the
+    # search passes
+    R = _gpu()
+    M = 1 << 24
+    x = workloads.laplace(2, M, seed=777)
+    x[1, M - 1] = 50.0    # the last column must be reachable
+    x[1, 0] = 49.0
+    for k in (64, 5000):
+        check(R, x, k, f"M=2^24 k={k}", modes=("exact", "smallest"))
+        xd = torch.from_numpy(x).cuda()
+        gv, gi = R.rtopk_rowwise(xd, k, 8)
+        ov, oi = oracle.topk_earlystop(x, k, 8)
+        assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(bits(gv.cpu().numpy()), bits(ov))
+        gv, gi, gt = R.rtopk_rowwise_eps(xd, k, 1e-3, want_iters=True)
+        ov, oi, ot = oracle.alg1(x, k, eps_rel=1e-3, collect=1)
+        assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(bits(gv.cpu().numpy()), bits(ov))
+        assert np.array_equal(gt.cpu().numpy(), ot)
+
+
 def test_streamed_rows_many_rows_guard_bands_and_nonfinite_inputs():
     R = _gpu()
     N, M, k = 300, 65600, 128
