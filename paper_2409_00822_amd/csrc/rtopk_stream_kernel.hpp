@@ -747,34 +747,39 @@ __global__ void __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_pe
   if (k <= kStreamWaves * kListPerWave) {
     uint2* list = reinterpret_cast<uint2*>(&s_hist[wave][0]);
     uint32_t wn = 0;  // candidates met by this wavefront
-    float nv[G];
-    if (u0 < u1 && u0 * kUnit + lane * G < M) stream_load<G>(row + u0 * kUnit + lane * G, nv);
-    for (int u = u0; u < u1 && wn <= (uint32_t)kListPerWave; ++u) {  // an overflowing list ends the attempt
-      const int c0 = u * kUnit + lane * G;
-      float v[G];
-      bool cand[G], any = false;
+    float ring[kAhead][G];
 #pragma unroll
-      for (int c = 0; c < G; ++c) v[c] = nv[c];
-      if (u + 1 < u1 && c0 + kUnit < M) stream_load<G>(row + c0 + kUnit, nv);
+    for (int j = 0; j < kAhead; ++j) load_slot(j, ring[j]);
+    for (int i = 0; i < u1 - u0 && wn <= (uint32_t)kListPerWave; i += kAhead) {  // an overflowing list ends the attempt
 #pragma unroll
-      for (int c = 0; c < G; ++c) {
-        const float key = keyof<NEG>(v[c]);
-        cand[c] = c0 < M && (key >= tA || (limB > 0 && key >= tB));
-        any = any || cand[c];
-      }
-      if (__builtin_amdgcn_ballot_w64(any) != 0) {  // most loads of a wide row hold no candidate
-        uint64_t m[G];
-        uint32_t pos = wn;
+      for (int j = 0; j < kAhead; ++j) {
+        const int u = u0 + i + j;
+        const int c0 = u * kUnit + lane * G;
+        const bool valid = u < u1 && c0 < M;
+        float v[G];
+        bool cand[G], any = false;
 #pragma unroll
         for (int c = 0; c < G; ++c) {
-          m[c] = __builtin_amdgcn_ballot_w64(cand[c]);
-          pos = lanes_below(m[c], pos);
+          v[c] = ring[j][c];
+          const float key = keyof<NEG>(v[c]);
+          cand[c] = valid && (key >= tA || (limB > 0 && key >= tB));
+          any = any || cand[c];
         }
+        load_slot(i + j + kAhead, ring[j]);
+        if (__builtin_amdgcn_ballot_w64(any) != 0) {  // most loads of a wide row hold no candidate
+          uint64_t m[G];
+          uint32_t pos = wn;
 #pragma unroll
-        for (int c = 0; c < G; ++c) {
-          if (cand[c] && pos < (uint32_t)kListPerWave) list[pos] = make_uint2(__float_as_uint(v[c]), (uint32_t)(c0 + c));
-          pos += cand[c] ? 1u : 0u;
-          wn += (uint32_t)__builtin_popcountll(m[c]);
+          for (int c = 0; c < G; ++c) {
+            m[c] = __builtin_amdgcn_ballot_w64(cand[c]);
+            pos = lanes_below(m[c], pos);
+          }
+#pragma unroll
+          for (int c = 0; c < G; ++c) {
+            if (cand[c] && pos < (uint32_t)kListPerWave) list[pos] = make_uint2(__float_as_uint(v[c]), (uint32_t)(c0 + c));
+            pos += cand[c] ? 1u : 0u;
+            wn += (uint32_t)__builtin_popcountll(m[c]);
+          }
         }
       }
     }
