@@ -799,10 +799,11 @@ def test_config4_eps_mode_full_size():
     assert_eps_parity(R, x, 64, 1e-4, tag="c4 eps=1e-4")
 
 
-@pytest.mark.parametrize("name,ks", [("x_wide32k", (256, 2048)), ("x_wide64k", (512,)), ("x_stream256k", (512,))])
+@pytest.mark.parametrize("name,ks", [("x_wide8k", (256,)), ("x_wide32k", (256, 2048)), ("x_wide64k", (512,)),
+                                     ("x_stream256k", (512,))])
 def test_workgroup_per_row_bench_workloads_full_size(name, ks):
-    # the workloads the workgroup-per-row kernels (row in registers, row streamed) are timed on, at the
-    # size that is timed
+    # the workloads the widest one-wavefront shape and the workgroup-per-row kernels (row in registers, row
+    # streamed) are timed on, at the size that is timed
     R = _gpu()
     x = workloads.make(name)
     for k in ks:

@@ -138,10 +138,12 @@ CONFIGS = {
     "c3_ties": dict(N=2_400_000, M=256, seed=3, dist="normal_ties", ks=(32,), max_iters=(8,), idx="uint8"),
     # wide rows
     "c4_wide": dict(N=65536, M=4096, seed=4, dist="laplace", ks=(64, 256), max_iters=(), idx="int32"),
-    # beyond the paper's widest row (Appendix B stops at M = 8192): one workgroup per row
+    # the paper's widest row (Appendix B: M = 8192), 128 values per lane of one wavefront
+    "x_wide8k": dict(N=32768, M=8192, seed=8, dist="laplace", ks=(256,), max_iters=(), idx="int32"),
+    # beyond the paper's widest row: one workgroup per row
     "x_wide32k": dict(N=8192, M=32768, seed=5, dist="laplace", ks=(256, 2048), max_iters=(), idx="int32"),
     "x_wide64k": dict(N=4096, M=65536, seed=6, dist="laplace", ks=(512,), max_iters=(), idx="int32"),
-    # rows that no longer fit a workgroup's registers: streamed, eight search steps per pass
+    # rows that no longer fit a workgroup's registers: streamed from memory
     "x_stream256k": dict(N=1024, M=262144, seed=7, dist="laplace", ks=(512,), max_iters=(), idx="int32"),
 }
 
