@@ -160,7 +160,9 @@ __device__ __forceinline__ void store_pair_if_below(uint32_t pos, uint32_t limit
 // (Measured on 1 GiB inputs: 4096 x 65536 exact 357 us with a workgroup per row, 347 us looping, 319 us with
 // 32 values loaded ahead, 324 us with 24, 361 us with 40, which spills.  The narrower shapes, which have two
 // to four workgroups on a compute unit whose phases overlap anyway, lose: 8192 x 32768 247 -> 278 us,
-// 16384 x 16384 249 -> 299 us when each resident workgroup walks a fixed share of the rows.)
+// 16384 x 16384 249 -> 299 us when each resident workgroup walks a fixed share of the rows.
+// Loading the other half as well, each group of the next row into the registers of the group the ranking
+// has just finished with, costs no register on paper but 23 spilled ones in practice: 319 -> 415 us.)
 #ifndef RTOPK_BLOCK_PERSIST_MIN_W
 #define RTOPK_BLOCK_PERSIST_MIN_W 16
 #endif
